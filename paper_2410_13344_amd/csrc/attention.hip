@@ -1,0 +1,224 @@
+// Tree-masked attention of the verify step.  Row n of a sequence (a tree node) attends to every
+// committed cache row 0..L-1 and to the tree rows L+m whose node m is n itself or an ancestor of n;
+// the ancestor sets are one 64-bit mask per node.  Tree attention is only named in the paper
+// (Sections 1 and 5.1); this is the ancestor-mask reading, with position L + depth(n).
+#include "common.h"
+
+namespace cerb {
+
+// ---------------------------------------------------------------------------------------------
+// Plain kernel, any element type: one wave per (row, head), lanes over the head dimension, online
+// softmax over the visible keys.  Used in fp32 reference mode and as a cross-check of the MFMA one.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int EPL>
+__global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
+  const int r = blockIdx.x, h = blockIdx.y;
+  if (r >= *a.rm.n_rows) return;
+  const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
+  const int L = a.rm.seq_L[b], Tb = a.rm.seq_T[b];
+  const int dh = a.dh, lane = threadIdx.x;
+  const unsigned long long mask = a.anc[node];
+  const T* q = reinterpret_cast<const T*>(a.q) + (size_t)r * a.nH * dh + h * dh;
+  const T* Kb = reinterpret_cast<const T*>(a.kv) + ((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap * dh;
+  const T* Vb = reinterpret_cast<const T*>(a.kv) + ((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap * dh;
+  const float scale = rsqrtf((float)dh);
+  float qv[EPL], o[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) { qv[e] = ld_f(q + lane + 64 * e) * scale; o[e] = 0.f; }
+  float m = -INFINITY, l = 0.f;
+  for (int p = 0; p < L + Tb; ++p) {
+    if (p >= L && !((mask >> (p - L)) & 1ull)) continue;
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s += qv[e] * ld_f(Kb + (size_t)p * dh + lane + 64 * e);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    const float mn = fmaxf(m, s);
+    const float corr = expf(m - mn);   // first key: exp(-inf) = 0
+    const float pw = expf(s - mn);
+    l = l * corr + pw;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) o[e] = o[e] * corr + pw * ld_f(Vb + (size_t)p * dh + lane + 64 * e);
+    m = mn;
+  }
+  T* out = reinterpret_cast<T*>(a.out) + (size_t)r * a.nH * dh + h * dh;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) st_f(out + lane + 64 * e, o[e] / l);
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA kernel (bf16).  Workgroup (chunk c, head h, sequence b) stages 128 keys of K and V in LDS
+// (16-byte pieces XOR-swizzled by the key index, so neither the row-wise K reads nor the transposed
+// V reads conflict), wave w takes query tile w (16 tree nodes).
+//   S^T = K Q^T      A = K rows (keys), B = Q (queries)  -> lane: query lane%16, keys 4*(lane/16)+v
+//   softmax stats per query: lane-local over its keys, then across the 4 lane groups
+//   O^T = V^T P^T    B = P^T taken straight from the S^T accumulators: contraction slot (g, e) of a
+//                    32-key block is key 4g+e (e<4) or 16+4g+e-4 (e>=4); A = V^T gathered from LDS
+//                    in the same slot order.
+// Writes unnormalised partial outputs with (max, sum) per query; k_attn_combine merges the chunks.
+// ---------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
+  constexpr int CK = 128;
+  constexpr int PPR = DH / 8;   // 16-byte pieces per row
+  constexpr int KS = DH / 32;
+  constexpr int DT = DH / 16;
+  constexpr int ROWB = DH * 2;
+  __shared__ __attribute__((aligned(16))) unsigned char sK[CK * ROWB];
+  __shared__ __attribute__((aligned(16))) unsigned char sV[CK * ROWB];
+
+  const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int L = a.rm.seq_L[b], Tb = a.rm.seq_T[b], row0 = a.rm.seq_row0[b];
+  const int NK = L + Tb;
+  const int key0 = c * CK;
+  if (Tb <= 0 || key0 >= NK) return;
+
+  const bf16_t* Kg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap * DH;
+  const bf16_t* Vg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap * DH;
+  for (int i = threadIdx.x; i < CK * PPR; i += 256) {
+    const int key = i / PPR, pc = i % PPR;
+    const int kabs = key0 + key;
+    uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+    if (kabs < NK) {
+      kk = reinterpret_cast<const uint4*>(Kg + (size_t)kabs * DH)[pc];
+      vv = reinterpret_cast<const uint4*>(Vg + (size_t)kabs * DH)[pc];
+    }
+    const int sw = pc ^ (key & (PPR - 1));
+    *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = kk;
+    *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = vv;
+  }
+  __syncthreads();
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lq = lane & 15, g = lane >> 4;
+  if (wave * 16 >= Tb) return;
+  const int qnode = wave * 16 + lq;
+  const bool qvalid = qnode < Tb;
+  const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.q) + (size_t)(row0 + min(qnode, Tb - 1)) * (a.nH * DH) + h * DH;
+  uint4 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
+  const unsigned long long amask = qvalid ? a.anc[qnode] : 0ull;
+  const float scale = rsqrtf((float)DH);
+
+  float s[CK / 16][4];
+  float m = -INFINITY;
+#pragma unroll
+  for (int kt = 0; kt < CK / 16; ++kt) {
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const int key = kt * 16 + lq;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int sw = (ks * 4 + g) ^ (key & (PPR - 1));
+      const uint4 kf = *reinterpret_cast<const uint4*>(sK + key * ROWB + sw * 16);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[ks]),
+                                                    acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int kabs = key0 + kt * 16 + 4 * g + v;
+      bool vis = kabs < L;
+      if (!vis && kabs < NK) vis = (amask >> (kabs - L)) & 1ull;
+      s[kt][v] = (vis && qvalid) ? acc[v] * scale : -INFINITY;
+      m = fmaxf(m, s[kt][v]);
+    }
+  }
+  m = fmaxf(m, __shfl_xor(m, 16, 64));
+  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  const float msafe = (m == -INFINITY) ? 0.f : m;
+  float lsum = 0.f;
+#pragma unroll
+  for (int kt = 0; kt < CK / 16; ++kt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float p = __expf(s[kt][v] - msafe);   // masked: exp(-inf) = 0
+      s[kt][v] = p;
+      lsum += p;
+    }
+  lsum += __shfl_xor(lsum, 16, 64);
+  lsum += __shfl_xor(lsum, 32, 64);
+
+  f32x4_t o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kp = 0; kp < CK / 32; ++kp) {
+    union { bf16_t u[8]; uint4 q; } pb;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      pb.u[e] = f32_to_bf16(s[2 * kp][e]);
+      pb.u[4 + e] = f32_to_bf16(s[2 * kp + 1][e]);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const int dh = dt * 16 + lq;
+      union { bf16_t u[8]; uint4 q; } va;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int key = kp * 32 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
+        const int sw = (dh >> 3) ^ (key & (PPR - 1));
+        va.u[e] = *reinterpret_cast<const bf16_t*>(sV + key * ROWB + sw * 16 + (dh & 7) * 2);
+      }
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va.q), __builtin_bit_cast(bf16x8_t, pb.q),
+                                                      o[dt], 0, 0, 0);
+    }
+  }
+
+  if (qvalid) {
+    const size_t slot = (((size_t)b * a.nH + h) * a.n_chunks_max + c) * 64 + qnode;
+    float* po = a.part_o + slot * DH;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      *reinterpret_cast<float4*>(po + dt * 16 + 4 * g) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+    if (g == 0) {
+      a.part_ml[slot * 2 + 0] = m;
+      a.part_ml[slot * 2 + 1] = lsum;
+    }
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
+  const int r = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
+  if (r >= *a.rm.n_rows) return;
+  const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
+  const int NK = a.rm.seq_L[b] + a.rm.seq_T[b];
+  const int nch = (NK + 127) / 128;
+  const size_t base = (((size_t)b * a.nH + h) * a.n_chunks_max) * 64 + node;
+  float M = -INFINITY;
+  for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[(base + (size_t)c * 64) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int c = 0; c < nch; ++c) {
+    const size_t slot = base + (size_t)c * 64;
+    const float w = __expf(a.part_ml[slot * 2] - M);
+    den += w * a.part_ml[slot * 2 + 1];
+    num += w * a.part_o[slot * DH + t];
+  }
+  reinterpret_cast<bf16_t*>(a.out)[(size_t)r * a.nH * DH + h * DH + t] = f32_to_bf16(num / den);
+}
+
+hipError_t launch_attention(const AttnArgs& a, int dtype, int use_mfma, hipStream_t s) {
+  if (dtype == 0 || !use_mfma) {
+    dim3 grid(a.rows_max, a.nH);
+    if (dtype == 0) {
+      if (a.dh == 64) hipLaunchKernelGGL((k_attn_simple<float, 1>), grid, dim3(64), 0, s, a);
+      else hipLaunchKernelGGL((k_attn_simple<float, 2>), grid, dim3(64), 0, s, a);
+    } else {
+      if (a.dh == 64) hipLaunchKernelGGL((k_attn_simple<bf16_t, 1>), grid, dim3(64), 0, s, a);
+      else hipLaunchKernelGGL((k_attn_simple<bf16_t, 2>), grid, dim3(64), 0, s, a);
+    }
+    return hipGetLastError();
+  }
+  dim3 grid(a.n_chunks_max, a.nH, a.batch);
+  dim3 cgrid(a.rows_max, a.nH);
+  if (a.dh == 64) {
+    hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((k_attn_combine<64>), cgrid, dim3(64), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(256), 0, s, a);
+    hipLaunchKernelGGL((k_attn_combine<128>), cgrid, dim3(128), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace cerb

@@ -1,0 +1,545 @@
+// Host side of the C ABI: validation, workspace layout, weight pre-tiling at init, and the launch
+// sequence of one decoding step (Algorithm 1 of the Cerberus paper in streaming form: the gate and
+// the heads run at the end of a forward pass and shape the next one).
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "step_kernels.h"
+
+using namespace cerb;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return fail(CERBERUS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+struct Bump {
+  unsigned char* base;
+  size_t off;
+  template <typename T>
+  T* take(size_t n) {
+    off = align_up(off, 256);
+    T* p = reinterpret_cast<T*>(base + off);  // base may be null when only sizing
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+}  // namespace
+
+struct cerberus_ctx {
+  cerberus_config cfg;
+  Dims D;
+  int device = 0;
+  int elem = 2;  // bytes per stored element
+  std::vector<int> parent, rank, depth;
+  std::vector<unsigned long long> anc;
+
+  // device memory, all inside the workspace
+  TreeDev tree{};
+  RowMap rm{};
+  float* inv_freq = nullptr;
+  int *last_row = nullptr, *path = nullptr, *g = nullptr;
+  float *x = nullptr, *h_last = nullptr, *part = nullptr, *attn_po = nullptr, *attn_ml = nullptr;
+  void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+  void* hsA[2] = {nullptr, nullptr};
+  float* hsF[2] = {nullptr, nullptr};
+  float* final_norm = nullptr;
+  std::vector<float*> attn_norm, ffn_norm, res_b;
+  std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down, pk_res, pk_fc;
+  void* pk_lm = nullptr;
+  size_t small_bytes = 0;  // everything before the packed weights
+
+  // weights as the kernels read them (packed copies in bf16 mode, the caller's in fp32 mode)
+  const void* embed = nullptr;
+  std::vector<const void*> wqkv, wo, wgu, wdown, res_w, head_fc;
+  const void* lm_head = nullptr;
+
+  size_t part_floats = 0;
+  int n_chunks_max = 0, R64 = 0;
+  cerberus_taps taps{};
+  int use_mfma_attn = 1, target_wgs = 512, max_split = 8;
+  std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
+  GemmBatch p_lm{}, p_fc{};
+  void* workspace = nullptr;
+  size_t workspace_bytes = 0;
+};
+
+namespace {
+
+int head_width(const cerberus_config& c, int i, int s) {
+  return (i >= 1 && c.special_block >= 0 && s >= c.special_block) ? 2 * c.d_model : c.d_model;
+}
+
+int kpad(const cerberus_config& c, int K) { return c.dtype == CERBERUS_BF16 ? (int)align_up(K, 256) : K; }
+
+int validate(const cerberus_config* c, const cerberus_tree* t) {
+  if (!c || !t) return fail(CERBERUS_ERR_ARG, "null config or tree");
+  if (c->dtype != CERBERUS_F32 && c->dtype != CERBERUS_BF16) return fail(CERBERUS_ERR_ARG, "dtype must be 0 (fp32) or 1 (bf16)");
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ffn < 1 || c->vocab < 1)
+    return fail(CERBERUS_ERR_ARG, "non-positive model dimension");
+  if (c->head_dim != 64 && c->head_dim != 128) return fail(CERBERUS_ERR_SHAPE, "head_dim must be 64 or 128");
+  if (c->d_model != c->n_heads * c->head_dim) return fail(CERBERUS_ERR_SHAPE, "d_model != n_heads * head_dim");
+  if (c->d_ffn % 8 || c->vocab % 16) return fail(CERBERUS_ERR_SHAPE, "d_ffn must be a multiple of 8 and vocab of 16");
+  if (c->n_cerb_heads < 1 || c->n_cerb_heads > CERBERUS_MAX_HEADS) return fail(CERBERUS_ERR_SHAPE, "n_cerb_heads out of 1..%d", CERBERUS_MAX_HEADS);
+  if (c->n_resblocks < 1 || c->n_resblocks > 16) return fail(CERBERUS_ERR_SHAPE, "n_resblocks out of 1..16");
+  if (c->special_block >= c->n_resblocks) return fail(CERBERUS_ERR_SHAPE, "special_block >= n_resblocks");
+  if (c->max_batch < 1 || c->max_batch > CERBERUS_MAX_BATCH) return fail(CERBERUS_ERR_SHAPE, "max_batch out of 1..%d", CERBERUS_MAX_BATCH);
+  if (c->topk < 1 || c->topk > CERBERUS_MAX_TOPK || c->topk > c->vocab) return fail(CERBERUS_ERR_SHAPE, "topk out of 1..%d", CERBERUS_MAX_TOPK);
+  if (c->kv_capacity < 1) return fail(CERBERUS_ERR_ARG, "kv_capacity < 1");
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 0.f)) return fail(CERBERUS_ERR_ARG, "rms_eps and rope_theta must be positive");
+  if (std::isnan(c->entropy_threshold)) return fail(CERBERUS_ERR_ARG, "entropy_threshold is NaN");
+  if (t->n_nodes < 1 || t->n_nodes > CERBERUS_MAX_TREE) return fail(CERBERUS_ERR_SHAPE, "tree size out of 1..%d", CERBERUS_MAX_TREE);
+  if (t->n_nodes > c->kv_capacity) return fail(CERBERUS_ERR_SHAPE, "tree larger than kv_capacity");
+  if (!t->parent || !t->rank) return fail(CERBERUS_ERR_ARG, "null tree arrays");
+  if (t->parent[0] != -1) return fail(CERBERUS_ERR_SHAPE, "parent[0] must be -1");
+  std::vector<int> depth(t->n_nodes, 0);
+  for (int n = 1; n < t->n_nodes; ++n) {
+    if (t->parent[n] < 0 || t->parent[n] >= n) return fail(CERBERUS_ERR_SHAPE, "parent[%d] must lie in 0..%d", n, n - 1);
+    depth[n] = depth[t->parent[n]] + 1;
+    if (depth[n] > c->n_cerb_heads) return fail(CERBERUS_ERR_SHAPE, "node %d is deeper than the number of heads", n);
+    if (t->rank[n] < 0 || t->rank[n] >= c->topk) return fail(CERBERUS_ERR_SHAPE, "rank[%d] must lie in 0..topk-1", n);
+  }
+  return CERBERUS_OK;
+}
+
+void fill_dims(cerberus_ctx* c, const cerberus_config* cfg, const cerberus_tree* t) {
+  c->cfg = *cfg;
+  Dims& D = c->D;
+  D.n_layers = cfg->n_layers; D.d = cfg->d_model; D.nH = cfg->n_heads; D.dh = cfg->head_dim; D.F = cfg->d_ffn;
+  D.Fpad = kpad(*cfg, cfg->d_ffn); D.V = cfg->vocab; D.Hc = cfg->n_cerb_heads; D.R = cfg->n_resblocks;
+  D.sb = cfg->special_block; D.dtype = cfg->dtype; D.Bmax = cfg->max_batch; D.cap = cfg->kv_capacity;
+  D.topk = cfg->topk; D.T = t->n_nodes; D.eps = cfg->rms_eps; D.threshold = cfg->entropy_threshold;
+  c->elem = cfg->dtype == CERBERUS_F32 ? 4 : 2;
+  c->R64 = (int)align_up((size_t)cfg->max_batch * t->n_nodes, 64);
+  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128);
+}
+
+// Assigns every workspace pointer of the context; with base == nullptr it only measures.
+size_t layout(cerberus_ctx* c, unsigned char* base) {
+  const Dims& D = c->D;
+  const cerberus_config& cfg = c->cfg;
+  Bump b{base, 0};
+  const int T = D.T, B = D.Bmax, Rmax = B * T, R64 = c->R64, d = D.d, el = c->elem;
+  c->tree.T = T;
+  c->tree.parent = b.take<int>(T);
+  c->tree.rank = b.take<int>(T);
+  c->tree.depth = b.take<int>(T);
+  c->tree.anc = b.take<unsigned long long>(T);
+  c->inv_freq = b.take<float>(D.dh / 2);
+  c->rm.n_rows = b.take<int>(1);
+  c->rm.seq_row0 = b.take<int>(B);
+  c->rm.seq_T = b.take<int>(B);
+  c->rm.seq_L = b.take<int>(B);
+  c->rm.row_seq = b.take<int>(Rmax);
+  c->rm.row_node = b.take<int>(Rmax);
+  c->rm.row_pos = b.take<int>(Rmax);
+  c->rm.row_tok = b.take<int>(Rmax);
+  c->last_row = b.take<int>(B);
+  c->path = b.take<int>((size_t)B * (D.Hc + 1));
+  c->g = b.take<int>(Rmax);
+  c->x = b.take<float>((size_t)R64 * d);
+  c->h_last = b.take<float>((size_t)R64 * d);
+  c->xn = b.take<unsigned char>((size_t)R64 * d * el);
+  c->q = b.take<unsigned char>((size_t)R64 * d * el);
+  c->attn = b.take<unsigned char>((size_t)R64 * d * el);
+  c->act = b.take<unsigned char>((size_t)R64 * D.Fpad * el);
+  const size_t nmax = (size_t)std::max(std::max(3 * d, 2 * D.F), D.V);
+  c->part_floats = 8 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
+  c->part = b.take<float>(c->part_floats);
+  const size_t slots = (size_t)B * D.nH * c->n_chunks_max * 64;
+  c->attn_po = b.take<float>(slots * D.dh);
+  c->attn_ml = b.take<float>(slots * 2);
+  for (int i = 0; i < 2; ++i) {
+    c->hsA[i] = b.take<unsigned char>((size_t)D.Hc * 16 * 2 * d * el);
+    c->hsF[i] = b.take<float>((size_t)D.Hc * 16 * 2 * d);
+  }
+  c->final_norm = b.take<float>(d);
+  c->attn_norm.assign(D.n_layers, nullptr);
+  c->ffn_norm.assign(D.n_layers, nullptr);
+  for (int l = 0; l < D.n_layers; ++l) { c->attn_norm[l] = b.take<float>(d); c->ffn_norm[l] = b.take<float>(d); }
+  c->res_b.assign((size_t)D.Hc * D.R, nullptr);
+  for (int i = 0; i < D.Hc; ++i)
+    for (int s = 0; s < D.R; ++s) c->res_b[i * D.R + s] = b.take<float>(head_width(cfg, i, s));
+  c->small_bytes = align_up(b.off, 256);
+  if (cfg.dtype == CERBERUS_BF16) {
+    auto pk = [&](int N, int K) { return (void*)b.take<bf16_t>((size_t)N * kpad(cfg, K)); };
+    c->pk_qkv.assign(D.n_layers, nullptr); c->pk_o.assign(D.n_layers, nullptr);
+    c->pk_gu.assign(D.n_layers, nullptr); c->pk_down.assign(D.n_layers, nullptr);
+    for (int l = 0; l < D.n_layers; ++l) {
+      c->pk_qkv[l] = pk(3 * d, d); c->pk_o[l] = pk(d, d); c->pk_gu[l] = pk(2 * D.F, d); c->pk_down[l] = pk(d, D.F);
+    }
+    c->pk_lm = pk(D.V, d);
+    c->pk_res.assign((size_t)D.Hc * D.R, nullptr);
+    c->pk_fc.assign(D.Hc, nullptr);
+    for (int i = 0; i < D.Hc; ++i) {
+      for (int s = 0; s < D.R; ++s) { const int w = head_width(cfg, i, s); c->pk_res[i * D.R + s] = pk(w, w); }
+      c->pk_fc[i] = pk(D.V, head_width(cfg, i, D.R - 1));
+    }
+  }
+  return align_up(b.off, 256);
+}
+
+// Split-K choice: enough workgroups to cover the chip a few times over, whole 256-wide k chunks.
+void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const* A, const int* lda, const void* const* W,
+               const int* N, const int* K, int out_rows, bool force_s1) {
+  std::memset(&g, 0, sizeof g);
+  g.n_prob = nprob;
+  const int cols = gemm_cols_per_wg(c->cfg.dtype);
+  int total_tiles = 0;
+  for (int p = 0; p < nprob; ++p) total_tiles += ceil_div(N[p], cols);
+  float* out = c->part;
+  int wg = 0;
+  for (int p = 0; p < nprob; ++p) {
+    GemmProb& P = g.p[p];
+    P.A = A[p]; P.W = W[p]; P.N = N[p]; P.lda = lda[p]; P.out_rows = out_rows;
+    if (c->cfg.dtype == CERBERUS_F32) {
+      P.K = K[p]; P.S = 1; P.kps = 0;
+    } else {
+      P.K = kpad(c->cfg, K[p]);
+      const int chunks = P.K / 256;
+      int S = force_s1 ? 1 : std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
+      S = std::min(S, std::min(c->max_split, chunks));
+      const int cps = ceil_div(chunks, S);
+      P.S = ceil_div(chunks, cps);
+      P.kps = cps * 8;
+    }
+    P.out = out;
+    out += (size_t)P.S * out_rows * P.N;
+    g.tile0[p] = wg;
+    wg += ceil_div(N[p], cols) * P.S;
+  }
+  g.tile0[nprob] = wg;
+}
+
+void build_plans(cerberus_ctx* c) {
+  const Dims& D = c->D;
+  const int d = D.d, L = D.n_layers;
+  c->p_qkv.resize(L); c->p_o.resize(L); c->p_gu.resize(L); c->p_down.resize(L);
+  for (int l = 0; l < L; ++l) {
+    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, &c->wqkv[l], &N, &K, c->R64, false); }
+    { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, &c->wo[l], &N, &K, c->R64, false); }
+    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, &c->wgu[l], &N, &K, c->R64, false); }
+    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, &c->wdown[l], &N, &K, c->R64, false); }
+  }
+  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, &c->lm_head, &N, &K, c->R64, false); }
+  c->p_res.resize(D.R);
+  const void* A[CERBERUS_MAX_HEADS]; const void* W[CERBERUS_MAX_HEADS];
+  int lda[CERBERUS_MAX_HEADS], N[CERBERUS_MAX_HEADS], K[CERBERUS_MAX_HEADS];
+  for (int s = 0; s < D.R; ++s) {
+    for (int i = 0; i < D.Hc; ++i) {
+      A[i] = (const unsigned char*)c->hsA[s & 1] + (size_t)i * 16 * 2 * d * c->elem;
+      W[i] = c->res_w[i * D.R + s];
+      lda[i] = 2 * d;
+      N[i] = K[i] = head_width(c->cfg, i, s);
+    }
+    plan_gemm(c, c->p_res[s], D.Hc, A, lda, W, N, K, 16, false);
+  }
+  for (int i = 0; i < D.Hc; ++i) {
+    A[i] = (const unsigned char*)c->hsA[D.R & 1] + (size_t)i * 16 * 2 * d * c->elem;
+    W[i] = c->head_fc[i];
+    lda[i] = 2 * d;
+    N[i] = D.V;
+    K[i] = head_width(c->cfg, i, D.R - 1);
+  }
+  plan_gemm(c, c->p_fc, D.Hc, A, lda, W, N, K, 16, true);
+}
+
+int check_state(const cerberus_ctx* c, const cerberus_state* st, int batch) {
+  if (!c || !st) return fail(CERBERUS_ERR_ARG, "null context or state");
+  if (batch < 1 || batch > c->cfg.max_batch) return fail(CERBERUS_ERR_ARG, "batch %d out of 1..%d", batch, c->cfg.max_batch);
+  if (!st->kv || !st->kv_len || !st->root_token || !st->cand || !st->gate_flag || !st->entropy || !st->accept_len ||
+      !st->accepted_tokens || !st->accepted_nodes || !st->status)
+    return fail(CERBERUS_ERR_ARG, "null pointer in cerberus_state");
+  return CERBERUS_OK;
+}
+
+int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, int rows_static, int rows_max,
+             const int* skip_flags, int n_skip, hipStream_t s) {
+  GemmBatch g = plan;
+  g.n_rows = n_rows;
+  g.rows_static = rows_static;
+  g.skip_flags = skip_flags;
+  g.n_skip = n_skip;
+  HIP_TRY(launch_gemm(g, c->cfg.dtype, rows_max, s));
+  return CERBERUS_OK;
+}
+
+#define TRY(expr)                     \
+  do {                                \
+    int rc_ = (expr);                 \
+    if (rc_ != CERBERUS_OK) return rc_; \
+  } while (0)
+
+int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream, int mode) {
+  TRY(check_state(c, st, batch));
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const Dims& D = c->D;
+  const RowMap& rm = c->rm;
+  const int rows_max = (mode == ASSEMBLE_FORCE_AR) ? batch : batch * D.T;
+  const size_t kv_layer_bytes = (size_t)2 * D.Bmax * D.nH * D.cap * D.dh * c->elem;
+
+  HIP_TRY(launch_assemble(D, c->tree, rm, *st, c->taps, batch, mode, s));
+  HIP_TRY(launch_embed(D, rm, c->embed, c->x, rows_max, s));
+
+  const GemmProb* prev = nullptr;  // GEMM whose partials are the pending residual
+  for (int l = 0; l < D.n_layers; ++l) {
+    HIP_TRY(launch_add_rmsnorm(D, rm, c->x, prev ? prev->out : nullptr, prev ? prev->S : 0,
+                               prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, nullptr, nullptr,
+                               rows_max, s));
+    TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
+    const GemmProb& pq = c->p_qkv[l].p[0];
+    void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
+    HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, rows_max, s));
+    AttnArgs aa{};
+    aa.q = c->q; aa.kv = kv_layer; aa.out = c->attn; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
+    aa.anc = c->tree.anc; aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
+    aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
+    HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
+    TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
+    const GemmProb& po = c->p_o[l].p[0];
+    HIP_TRY(launch_add_rmsnorm(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, nullptr,
+                               nullptr, rows_max, s));
+    TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
+    const GemmProb& pg = c->p_gu[l].p[0];
+    HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, rows_max, s));
+    TRY(run_gemm(c, c->p_down[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
+    prev = &c->p_down[l].p[0];
+  }
+  HIP_TRY(launch_add_rmsnorm(D, rm, c->x, prev->out, prev->S, (size_t)prev->out_rows * prev->N, c->final_norm, c->xn,
+                             c->h_last, c->taps.h_last, rows_max, s));
+  TRY(run_gemm(c, c->p_lm, rm.n_rows, 0, rows_max, nullptr, 0, s));
+  const GemmProb& pl = c->p_lm.p[0];
+  HIP_TRY(launch_row_argmax(D, rm, pl.out, pl.S, (size_t)pl.out_rows * pl.N, c->g, c->taps, rows_max, s));
+
+  HIP_TRY(launch_accept(D, c->tree, rm, c->g, rm.row_tok, *st, c->path, c->last_row, batch, s));
+  if (mode != ASSEMBLE_FORCE_AR) HIP_TRY(launch_compact(D, rm, *st, c->path, batch, s));
+  HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, c->taps.forced_gate_hidden, rm.seq_T, batch, st->entropy,
+                      st->gate_flag, s));
+
+  // heads: skipped on the device when every sequence's gate chose the auto-regressive step
+  HIP_TRY(launch_heads_prepare(D, c->h_last, c->last_row, c->hsF[0], c->hsA[0], batch, s));
+  for (int st_i = 0; st_i < D.R; ++st_i) {
+    TRY(run_gemm(c, c->p_res[st_i], nullptr, batch, batch, st->gate_flag, batch, s));
+    ResFinishArgs ra{};
+    for (int i = 0; i < D.Hc; ++i) {
+      const GemmProb& P = c->p_res[st_i].p[i];
+      ra.part[i] = P.out; ra.S[i] = P.S; ra.pstride[i] = (size_t)P.out_rows * P.N; ra.width[i] = P.N;
+      ra.bias[i] = c->res_b[i * D.R + st_i];
+    }
+    HIP_TRY(launch_resblock_finish(D, ra, c->hsF[st_i & 1], c->hsF[(st_i + 1) & 1], c->hsA[(st_i + 1) & 1],
+                                   (st_i + 1 == D.sb) ? 1 : 0, batch, s));
+  }
+  TRY(run_gemm(c, c->p_fc, nullptr, batch, batch, st->gate_flag, batch, s));
+  TopkArgs ta{};
+  ta.seq_T = rm.seq_T;
+  for (int i = 0; i < D.Hc; ++i) ta.logits[i] = c->p_fc.p[i].out;
+  HIP_TRY(launch_topk(D, ta, *st, c->taps, batch, s));
+  return CERBERUS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* cerberus_last_error(void) { return g_err; }
+
+size_t cerberus_workspace_bytes(const cerberus_config* cfg, const cerberus_tree* tree) {
+  if (validate(cfg, tree) != CERBERUS_OK) return 0;
+  cerberus_ctx tmp;
+  fill_dims(&tmp, cfg, tree);
+  return layout(&tmp, nullptr);
+}
+
+int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus_weights* w, const cerberus_tree* tree,
+                  void* workspace, size_t workspace_bytes) {
+  if (!out) return fail(CERBERUS_ERR_ARG, "null out pointer");
+  *out = nullptr;
+  TRY(validate(cfg, tree));
+  if (!w || !workspace) return fail(CERBERUS_ERR_ARG, "null weights or workspace");
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(CERBERUS_ERR_ARG, "workspace must be 256-byte aligned");
+  if (!w->embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm || !w->w_gate_up ||
+      !w->w_down || !w->res_w || !w->res_b || !w->head_fc)
+    return fail(CERBERUS_ERR_ARG, "null pointer in cerberus_weights");
+  for (int l = 0; l < cfg->n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate_up[l] || !w->w_down[l])
+      return fail(CERBERUS_ERR_ARG, "null weight pointer in layer %d", l);
+  for (int i = 0; i < cfg->n_cerb_heads; ++i) {
+    if (!w->head_fc[i]) return fail(CERBERUS_ERR_ARG, "null head_fc[%d]", i);
+    for (int s = 0; s < cfg->n_resblocks; ++s)
+      if (!w->res_w[i * cfg->n_resblocks + s] || !w->res_b[i * cfg->n_resblocks + s])
+        return fail(CERBERUS_ERR_ARG, "null Resblock weight of head %d block %d", i, s);
+  }
+
+  cerberus_ctx* c = new (std::nothrow) cerberus_ctx;
+  if (!c) return fail(CERBERUS_ERR_ARG, "out of host memory");
+  fill_dims(c, cfg, tree);
+  const size_t need = layout(c, reinterpret_cast<unsigned char*>(workspace));
+  if (workspace_bytes < need) {
+    delete c;
+    return fail(CERBERUS_ERR_CAPACITY, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
+  }
+  c->workspace = workspace;
+  c->workspace_bytes = workspace_bytes;
+  const Dims& D = c->D;
+  const int T = D.T, d = D.d;
+
+  c->parent.assign(tree->parent, tree->parent + T);
+  c->rank.assign(tree->rank, tree->rank + T);
+  c->depth.assign(T, 0);
+  c->anc.assign(T, 0ull);
+  for (int n = 0; n < T; ++n) {
+    if (n > 0) { c->depth[n] = c->depth[c->parent[n]] + 1; c->anc[n] = c->anc[c->parent[n]]; }
+    c->anc[n] |= 1ull << n;
+  }
+  std::vector<float> inv(D.dh / 2);
+  for (int j = 0; j < D.dh / 2; ++j) inv[j] = (float)std::pow((double)cfg->rope_theta, -2.0 * j / D.dh);
+
+  auto cleanup = [&](int rc) { delete c; return rc; };
+#define HIP_INIT(expr)                                                                                      \
+  do {                                                                                                      \
+    hipError_t e_ = (expr);                                                                                 \
+    if (e_ != hipSuccess) return cleanup(fail(CERBERUS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)));   \
+  } while (0)
+
+  HIP_INIT(hipGetDevice(&c->device));
+  HIP_INIT(hipMemset(workspace, 0, c->small_bytes));
+  HIP_INIT(hipMemcpy((void*)c->tree.parent, c->parent.data(), T * sizeof(int), hipMemcpyHostToDevice));
+  HIP_INIT(hipMemcpy((void*)c->tree.rank, c->rank.data(), T * sizeof(int), hipMemcpyHostToDevice));
+  HIP_INIT(hipMemcpy((void*)c->tree.depth, c->depth.data(), T * sizeof(int), hipMemcpyHostToDevice));
+  HIP_INIT(hipMemcpy((void*)c->tree.anc, c->anc.data(), T * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  HIP_INIT(hipMemcpy(c->inv_freq, inv.data(), inv.size() * sizeof(float), hipMemcpyHostToDevice));
+
+  hipStream_t s0 = nullptr;
+  HIP_INIT(launch_to_f32(w->final_norm, c->final_norm, d, D.dtype, s0));
+  for (int l = 0; l < D.n_layers; ++l) {
+    HIP_INIT(launch_to_f32(w->attn_norm[l], c->attn_norm[l], d, D.dtype, s0));
+    HIP_INIT(launch_to_f32(w->ffn_norm[l], c->ffn_norm[l], d, D.dtype, s0));
+  }
+  for (int i = 0; i < D.Hc; ++i)
+    for (int s = 0; s < D.R; ++s)
+      HIP_INIT(launch_to_f32(w->res_b[i * D.R + s], c->res_b[i * D.R + s], head_width(*cfg, i, s), D.dtype, s0));
+
+  c->embed = w->embed;
+  c->wqkv.assign(D.n_layers, nullptr); c->wo.assign(D.n_layers, nullptr);
+  c->wgu.assign(D.n_layers, nullptr); c->wdown.assign(D.n_layers, nullptr);
+  c->res_w.assign((size_t)D.Hc * D.R, nullptr); c->head_fc.assign(D.Hc, nullptr);
+  if (D.dtype == CERBERUS_F32) {
+    for (int l = 0; l < D.n_layers; ++l) {
+      c->wqkv[l] = w->wqkv[l]; c->wo[l] = w->wo[l]; c->wgu[l] = w->w_gate_up[l]; c->wdown[l] = w->w_down[l];
+    }
+    c->lm_head = w->lm_head;
+    for (int i = 0; i < D.Hc; ++i) {
+      for (int s = 0; s < D.R; ++s) c->res_w[i * D.R + s] = w->res_w[i * D.R + s];
+      c->head_fc[i] = w->head_fc[i];
+    }
+  } else {
+    auto pack = [&](const void* src, void* dst, int N, int K) {
+      return launch_pack_weight(reinterpret_cast<const bf16_t*>(src), dst, N, K, kpad(*cfg, K), s0);
+    };
+    for (int l = 0; l < D.n_layers; ++l) {
+      HIP_INIT(pack(w->wqkv[l], c->pk_qkv[l], 3 * d, d));
+      HIP_INIT(pack(w->wo[l], c->pk_o[l], d, d));
+      HIP_INIT(pack(w->w_gate_up[l], c->pk_gu[l], 2 * D.F, d));
+      HIP_INIT(pack(w->w_down[l], c->pk_down[l], d, D.F));
+      c->wqkv[l] = c->pk_qkv[l]; c->wo[l] = c->pk_o[l]; c->wgu[l] = c->pk_gu[l]; c->wdown[l] = c->pk_down[l];
+    }
+    HIP_INIT(pack(w->lm_head, c->pk_lm, D.V, d));
+    c->lm_head = c->pk_lm;
+    for (int i = 0; i < D.Hc; ++i) {
+      for (int s = 0; s < D.R; ++s) {
+        const int wd = head_width(*cfg, i, s);
+        HIP_INIT(pack(w->res_w[i * D.R + s], c->pk_res[i * D.R + s], wd, wd));
+        c->res_w[i * D.R + s] = c->pk_res[i * D.R + s];
+      }
+      HIP_INIT(pack(w->head_fc[i], c->pk_fc[i], D.V, head_width(*cfg, i, D.R - 1)));
+      c->head_fc[i] = c->pk_fc[i];
+    }
+  }
+  HIP_INIT(hipDeviceSynchronize());
+#undef HIP_INIT
+  build_plans(c);
+  *out = c;
+  return CERBERUS_OK;
+}
+
+int cerberus_verify_step(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch, void* stream) {
+  return run_step(ctx, st, batch, stream, ASSEMBLE_BY_FLAG);
+}
+
+int cerberus_ar_step(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch, void* stream) {
+  return run_step(ctx, st, batch, stream, ASSEMBLE_FORCE_AR);
+}
+
+int cerberus_gate(cerberus_ctx* ctx, const float* hidden, int32_t rows, float* entropy_out, int32_t* flag_out, void* stream) {
+  if (!ctx || !hidden || !entropy_out || !flag_out) return fail(CERBERUS_ERR_ARG, "null argument");
+  if (rows < 0) return fail(CERBERUS_ERR_ARG, "rows < 0");
+  if (rows == 0) return CERBERUS_OK;
+  HIP_TRY(launch_gate(ctx->D.d, ctx->D.threshold, hidden, nullptr, nullptr, nullptr, rows, entropy_out, flag_out,
+                      reinterpret_cast<hipStream_t>(stream)));
+  return CERBERUS_OK;
+}
+
+int cerberus_accept(cerberus_ctx* ctx, const int32_t* node_argmax, const int32_t* node_token, const cerberus_state* st,
+                    int32_t batch, void* stream) {
+  TRY(check_state(ctx, st, batch));
+  if (!node_argmax || !node_token) return fail(CERBERUS_ERR_ARG, "null node arrays");
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  cerberus_taps none{};
+  HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, s));
+  HIP_TRY(launch_accept(ctx->D, ctx->tree, ctx->rm, node_argmax, node_token, *st, ctx->path, ctx->last_row, batch, s));
+  HIP_TRY(launch_compact(ctx->D, ctx->rm, *st, ctx->path, batch, s));
+  return CERBERUS_OK;
+}
+
+int cerberus_set_taps(cerberus_ctx* ctx, const cerberus_taps* taps) {
+  if (!ctx) return fail(CERBERUS_ERR_ARG, "null context");
+  if (taps) ctx->taps = *taps;
+  else std::memset(&ctx->taps, 0, sizeof ctx->taps);
+  return CERBERUS_OK;
+}
+
+int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
+  if (!ctx || !name) return fail(CERBERUS_ERR_ARG, "null argument");
+  const std::string n(name);
+  if (n == "attn_mfma") {
+    if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "attn_mfma must be 0 or 1");
+    ctx->use_mfma_attn = value;
+  } else if (n == "gemm_target_wgs") {
+    if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "gemm_target_wgs out of 1..65536");
+    ctx->target_wgs = value;
+    build_plans(ctx);
+  } else if (n == "gemm_max_split") {
+    if (value < 1 || value > 8) return fail(CERBERUS_ERR_ARG, "gemm_max_split out of 1..8");
+    ctx->max_split = value;
+    build_plans(ctx);
+  } else {
+    return fail(CERBERUS_ERR_ARG, "unknown parameter '%s'", name);
+  }
+  return CERBERUS_OK;
+}
+
+void cerberus_destroy(cerberus_ctx* ctx) { delete ctx; }
+
+}  // extern "C"

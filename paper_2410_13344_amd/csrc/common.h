@@ -1,0 +1,101 @@
+// Shared declarations of the Cerberus verify-step kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cerb {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float ld_f(const T* p);
+template <> __device__ __forceinline__ float ld_f<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld_f<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void st_f(T* p, float v);
+template <> __device__ __forceinline__ void st_f<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st_f<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---------------------------------------------------------------------------------------------
+// per-step row map: packed rows of all sequences (sequence b owns rows seq_row0[b] .. +seq_T[b])
+// ---------------------------------------------------------------------------------------------
+struct RowMap {
+  int* n_rows;    // [1]
+  int* seq_row0;  // [B]
+  int* seq_T;     // [B] tree size used this step: T or 1
+  int* seq_L;     // [B] kv_len at the start of the step
+  int* row_seq;   // [Rmax]
+  int* row_node;  // [Rmax]
+  int* row_pos;   // [Rmax]
+  int* row_tok;   // [Rmax]
+};
+
+struct TreeDev {
+  int T;
+  const int* parent;            // [T]
+  const int* rank;              // [T]
+  const int* depth;             // [T]
+  const unsigned long long* anc;  // [T] bit m set: node m is the node itself or an ancestor
+};
+
+// ---------------------------------------------------------------------------------------------
+// GEMM launch description: out[split][row][n] = sum_k A[row][k] * W[n][k] over the split's k range
+// ---------------------------------------------------------------------------------------------
+struct GemmProb {
+  const void* A;  // [rows_alloc][lda], element type of the mode
+  const void* W;  // bf16 mode: MFMA-tile packed; f32 mode: row-major [N][K]
+  float* out;     // [S][out_rows][N]
+  int N, K;       // bf16 mode: K is the padded K (multiple of 32)
+  int lda;
+  int out_rows;
+  int S;          // split-K factor
+  int kps;        // k-steps (of 32) per split, multiple of 8
+};
+
+enum { GEMM_MAX_PROB = 8 };
+
+struct GemmBatch {
+  GemmProb p[GEMM_MAX_PROB];
+  int n_prob;
+  int tile0[GEMM_MAX_PROB + 1];  // first workgroup of every problem
+  const int* n_rows;             // device row count, or nullptr -> rows_static
+  int rows_static;
+  const int* skip_flags;         // if non-null and all n_skip flags are non-zero: nothing to do
+  int n_skip;
+};
+
+// launchers (defined next to their kernels)
+hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t s);
+hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int Kpad, hipStream_t s);
+int gemm_cols_per_wg(int dtype);
+
+struct AttnArgs {
+  const void* q;     // [rows][nH*dh]
+  const void* kv;    // layer base: [2][Bmax][nH][cap][dh]
+  void* out;         // [rows][nH*dh] attention output (GEMM A operand)
+  float* part_o;     // [B][nH][n_chunks_max][64][dh]
+  float* part_ml;    // [B][nH][n_chunks_max][64][2]
+  RowMap rm;
+  const unsigned long long* anc;
+  int batch, Bmax, nH, dh, cap, T;
+  int chunk;         // keys per workgroup
+  int n_chunks_max;
+  int rows_max;
+  int* status;
+};
+hipError_t launch_attention(const AttnArgs& a, int dtype, int use_mfma, hipStream_t s);
+
+}  // namespace cerb

@@ -1,0 +1,213 @@
+// Skinny GEMMs of the verify step: out[row][n] = sum_k A[row][k] * W[n][k] for 1..64 tree-token
+// rows (per row block) against weight matrices that are read exactly once per step.  The work is
+// weight streaming: every wave pulls its own 16-column slab of the pre-tiled weights straight from
+// HBM into registers in 1 KB fully coalesced loads, several loads in flight, while the few
+// activation rows are staged through LDS and shared by the four waves of the workgroup.
+#include "common.h"
+
+namespace cerb {
+
+// ---------------------------------------------------------------------------------------------
+// Weight pre-tiling (init time).  Packed layout, in 16-byte pieces:
+//   piece[(sub * ksteps + ks) * 64 + lane] = W[sub*16 + lane%16][ks*32 + (lane/16)*8 .. +8]
+// i.e. one 1 KB block per (16 output columns, 32 k) holds exactly the B operand of one
+// v_mfma_f32_16x16x32_bf16, lane by lane; consecutive k-steps of a column slab are contiguous.
+// Columns k >= K (padding up to Kpad) are zero.
+// ---------------------------------------------------------------------------------------------
+__global__ void k_pack_weight(const bf16_t* __restrict__ W, uint4* __restrict__ out, int N, int K, int Kpad) {
+  const int ksteps = Kpad / 32;
+  const size_t total = (size_t)(N / 16) * ksteps * 64;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int lane = (int)(i % 64);
+    const size_t blk = i / 64;
+    const int ks = (int)(blk % ksteps);
+    const int sub = (int)(blk / ksteps);
+    const int n = sub * 16 + (lane % 16);
+    const int k = ks * 32 + (lane / 16) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (k < K) v = *reinterpret_cast<const uint4*>(W + (size_t)n * K + k);  // K % 8 == 0
+    out[i] = v;
+  }
+}
+
+hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int Kpad, hipStream_t s) {
+  const size_t total = (size_t)(N / 16) * (Kpad / 32) * 64;
+  int blocks = (int)((total + 255) / 256);
+  if (blocks > 65535) blocks = 65535;
+  hipLaunchKernelGGL(k_pack_weight, dim3(blocks), dim3(256), 0, s, W, reinterpret_cast<uint4*>(packed), N, K, Kpad);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA GEMM.  Workgroup = 4 waves; wave w owns NSUB adjacent 16-column slabs; a workgroup
+// covers 64*NSUB columns, MT*16 rows and one split of K (whole chunks of 256 k).  A is staged
+// through a double-buffered LDS tile per chunk (row stride 528 B: the 16 lanes of an MFMA row
+// group then hit 64 distinct banks); the main loop has no branches, so the weight loads stay in
+// flight across chunk boundaries.
+// ---------------------------------------------------------------------------------------------
+constexpr int kLdsRow = 528;   // 256 bf16 + 16 B pad
+constexpr int kRing = 4;       // k-steps of weights in flight per wave
+
+__device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
+  if (g.skip_flags == nullptr) return false;
+  bool all = true;
+  for (int i = 0; i < g.n_skip; ++i) all = all && (g.skip_flags[i] != 0);
+  return all;
+}
+
+template <int MT, int NSUB>
+__global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
+  if (gemm_skip(g)) return;
+  const int rows = g.n_rows ? *g.n_rows : g.rows_static;
+  const int m0 = blockIdx.y * (MT * 16);
+  if (m0 >= rows) return;
+
+  int pi = 0;
+  while (pi + 1 < g.n_prob && (int)blockIdx.x >= g.tile0[pi + 1]) ++pi;
+  const GemmProb P = g.p[pi];
+  const int local = (int)blockIdx.x - g.tile0[pi];
+  const int split = local % P.S;
+  const int ntile = local / P.S;
+  const int ksteps = P.K / 32;               // K is a multiple of 256: whole chunks only
+  const int ks0 = split * P.kps;             // kps is a multiple of 8
+  const int ks1 = min(ks0 + P.kps, ksteps);
+  const int nchunks = (ks1 - ks0) / 8;
+  if (nchunks <= 0) return;                  // uniform over the workgroup
+
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int nsub_total = P.N / 16;
+
+  constexpr int kBuf = MT * 16 * kLdsRow;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBuf];
+
+  const uint4* wp[NSUB];
+  int sub[NSUB];
+#pragma unroll
+  for (int j = 0; j < NSUB; ++j) {
+    sub[j] = (ntile * 4 + wave) * NSUB + j;
+    const int sc = min(sub[j], nsub_total - 1);  // clamp: out-of-range slabs load valid memory, store nothing
+    wp[j] = reinterpret_cast<const uint4*>(P.W) + (size_t)sc * ksteps * 64 + lane;
+  }
+
+  f32x4_t acc[MT][NSUB];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int j = 0; j < NSUB; ++j) acc[mt][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  // activation chunk c+1 travels global -> registers while chunk c is consumed from LDS
+  constexpr int kApt = MT * 2;  // 16-byte pieces per thread per chunk
+  const bf16_t* A = reinterpret_cast<const bf16_t*>(P.A);
+  uint4 areg[kApt];
+  auto load_a = [&](int chunk) {
+#pragma unroll
+    for (int i = 0; i < kApt; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int r = idx >> 5, pc = idx & 31;
+      areg[i] = *reinterpret_cast<const uint4*>(A + (size_t)(m0 + r) * P.lda + (size_t)(ks0 + chunk * 8) * 32 + pc * 8);
+    }
+  };
+  auto store_a = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < kApt; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int r = idx >> 5, pc = idx & 31;
+      *reinterpret_cast<uint4*>(lds + buf * kBuf + r * kLdsRow + pc * 16) = areg[i];
+    }
+  };
+
+  load_a(0);
+  uint4 ring[kRing][NSUB];
+#pragma unroll
+  for (int i = 0; i < kRing; ++i)
+#pragma unroll
+    for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + i, ks1 - 1) * 64];
+  store_a(0);
+  __syncthreads();
+
+  const int a_off = (lane & 15) * kLdsRow + (lane >> 4) * 16;
+  for (int c = 0; c < nchunks; ++c) {
+    load_a(min(c + 1, nchunks - 1));
+    const unsigned char* L = lds + (c & 1) * kBuf + a_off;
+    const int kb = ks0 + c * 8;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      uint4 b[NSUB];
+#pragma unroll
+      for (int j = 0; j < NSUB; ++j) {
+        b[j] = ring[s % kRing][j];
+        ring[s % kRing][j] = wp[j][(size_t)min(kb + s + kRing, ks1 - 1) * 64];
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + s * 64);
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j)
+          acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                               __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);
+      }
+    }
+    store_a((c + 1) & 1);
+    __syncthreads();
+  }
+
+  // D layout: lane holds column lane%16, rows 4*(lane/16) + v
+  float* out = P.out + (size_t)split * P.out_rows * P.N;
+#pragma unroll
+  for (int j = 0; j < NSUB; ++j) {
+    if (sub[j] >= nsub_total) continue;
+    const int col = sub[j] * 16 + (lane & 15);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = m0 + mt * 16 + (lane >> 4) * 4 + v;
+        if (row < rows) out[(size_t)row * P.N + col] = acc[mt][j][v];
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 reference-mode GEMM (small models only): one thread per output column, 4 rows per block
+// pass, plain sequential fp32 accumulation.  Workgroup = 64 columns x 16 rows.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_gemm_f32(const GemmBatch g) {
+  if (gemm_skip(g)) return;
+  const int rows = g.n_rows ? *g.n_rows : g.rows_static;
+  const int m0 = blockIdx.y * 16;
+  if (m0 >= rows) return;
+  int pi = 0;
+  while (pi + 1 < g.n_prob && (int)blockIdx.x >= g.tile0[pi + 1]) ++pi;
+  const GemmProb P = g.p[pi];
+  const int ntile = (int)blockIdx.x - g.tile0[pi];
+  const int col = ntile * 64 + (threadIdx.x & 63);
+  if (col >= P.N) return;
+  const float* A = reinterpret_cast<const float*>(P.A);
+  const float* Wr = reinterpret_cast<const float*>(P.W) + (size_t)col * P.K;
+  for (int r = m0 + (threadIdx.x >> 6); r < min(m0 + 16, rows); r += 4) {
+    const float* a = A + (size_t)r * P.lda;
+    float acc = 0.f;
+    for (int k = 0; k < P.K; ++k) acc = fmaf(a[k], Wr[k], acc);
+    P.out[(size_t)r * P.N + col] = acc;
+  }
+}
+
+int gemm_cols_per_wg(int dtype) { return dtype == 0 ? 64 : 128; }
+
+hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t s) {
+  const int wgs = g.tile0[g.n_prob];
+  if (wgs <= 0 || rows_max <= 0) return hipSuccess;
+  if (dtype == 0) {
+    hipLaunchKernelGGL(k_gemm_f32, dim3(wgs, (rows_max + 15) / 16), dim3(256), 0, s, g);
+  } else if (rows_max <= 16) {
+    hipLaunchKernelGGL((k_gemm_bf16<1, 2>), dim3(wgs, 1), dim3(256), 0, s, g);
+  } else if (rows_max <= 32) {
+    hipLaunchKernelGGL((k_gemm_bf16<2, 2>), dim3(wgs, 1), dim3(256), 0, s, g);
+  } else {
+    hipLaunchKernelGGL((k_gemm_bf16<4, 2>), dim3(wgs, (rows_max + 63) / 64), dim3(256), 0, s, g);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace cerb

@@ -1,0 +1,496 @@
+// Small kernels of the verify step: tree assembly and embedding, residual + RMSNorm, RoPE and KV
+// write, SwiGLU, per-node argmax, acceptance walk, KV compaction, entropy gate, the element-wise
+// half of the Cerberus heads' Resblocks, and per-head top-k.  All are bandwidth-trivial next to
+// the weight stream; each is written for clarity and coalesced access.
+#include "step_kernels.h"
+
+#include <limits.h>
+
+namespace cerb {
+
+// ---------------------------------------------------------------------------------------------
+// block reductions (blockDim.x a multiple of 64, at most 256)
+// ---------------------------------------------------------------------------------------------
+template <typename V>
+__device__ __forceinline__ V block_sum(V v, V* sh) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[wave] = v;
+  __syncthreads();
+  V t = sh[0];
+  for (int w = 1; w < nw; ++w) t += sh[w];
+  return t;
+}
+
+__device__ __forceinline__ float block_max(float v, float* sh) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[wave] = v;
+  __syncthreads();
+  float t = sh[0];
+  for (int w = 1; w < nw; ++w) t = fmaxf(t, sh[w]);
+  return t;
+}
+
+// best = larger value, ties to the lower index
+__device__ __forceinline__ void better(float& bv, int& bi, float v, int i) {
+  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+__device__ __forceinline__ void block_argmax(float& bv, int& bi, float* shv, int* shi) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    better(bv, bi, ov, oi);
+  }
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { shv[wave] = bv; shi[wave] = bi; }
+  __syncthreads();
+  bv = shv[0]; bi = shi[0];
+  for (int w = 1; w < nw; ++w) better(bv, bi, shv[w], shi[w]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tree assembly (Algorithm 1 line 1 and the Candidates tuple of lines 11-12): which rows this step
+// has, and the token / position of each.  One block; sequences pack their rows back to back.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr, const RowMap rm, const cerberus_state st,
+                                                 const cerberus_taps tp, int batch, int mode) {
+  __shared__ int sT[CERBERUS_MAX_BATCH], sL[CERBERUS_MAX_BATCH], sRow0[CERBERUS_MAX_BATCH];
+  const int t = threadIdx.x;
+  if (t < batch) {
+    const int L = st.kv_len[t];
+    int Tb = tr.T;
+    if (mode == ASSEMBLE_FORCE_AR || (mode == ASSEMBLE_BY_FLAG && st.gate_flag[t] != 0)) Tb = 1;
+    if (L < 0 || L + Tb > D.cap) {  // the sequence sits this step out
+      Tb = 0;
+      atomicOr(st.status, (int)CERBERUS_DEV_KV_OVERFLOW);
+    }
+    sT[t] = Tb;
+    sL[t] = L;
+  }
+  __syncthreads();
+  if (t == 0) {
+    int r = 0;
+    for (int b = 0; b < batch; ++b) { sRow0[b] = r; r += sT[b]; }
+    *rm.n_rows = r;
+  }
+  __syncthreads();
+  if (t < batch) { rm.seq_T[t] = sT[t]; rm.seq_L[t] = sL[t]; rm.seq_row0[t] = sRow0[t]; }
+  for (int b = 0; b < batch; ++b) {
+    for (int node = t; node < sT[b]; node += blockDim.x) {
+      const int r = sRow0[b] + node;
+      const int dep = tr.depth[node];
+      rm.row_seq[r] = b;
+      rm.row_node[r] = node;
+      rm.row_pos[r] = sL[b] + dep;
+      if (mode != ASSEMBLE_FULL_TREE) {
+        int tok = node == 0 ? st.root_token[b] : st.cand[(b * D.Hc + dep - 1) * D.topk + tr.rank[node]];
+        if (tok < 0 || tok >= D.V) { atomicOr(st.status, (int)CERBERUS_DEV_BAD_TOKEN); tok = 0; }
+        rm.row_tok[r] = tok;
+        if (tp.node_token) tp.node_token[b * tr.T + node] = tok;
+      }
+    }
+  }
+}
+
+hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, const cerberus_state& st,
+                           const cerberus_taps& tp, int batch, int mode, hipStream_t s) {
+  hipLaunchKernelGGL(k_assemble, dim3(1), dim3(64), 0, s, D, tr, rm, st, tp, batch, mode);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(const T* __restrict__ embed, const RowMap rm, float* __restrict__ x, int d) {
+  const int r = blockIdx.x;
+  if (r >= *rm.n_rows) return;
+  const T* e = embed + (size_t)rm.row_tok[r] * d;
+  for (int c = threadIdx.x; c < d; c += 256) x[(size_t)r * d + c] = ld_f(e + c);
+}
+
+hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, int rows_max, hipStream_t s) {
+  if (D.dtype == 0) hipLaunchKernelGGL((k_embed<float>), dim3(rows_max), dim3(256), 0, s, (const float*)embed, rm, x, D.d);
+  else hipLaunchKernelGGL((k_embed<bf16_t>), dim3(rows_max), dim3(256), 0, s, (const bf16_t*)embed, rm, x, D.d);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// x += sum of the previous GEMM's split-K partials (the residual add), then RMSNorm:
+// out = x * gain / sqrt(mean(x^2) + eps), rounded to the GEMM input type.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ part, int S,
+                                                     size_t pstride, const float* __restrict__ gain, float eps,
+                                                     T* __restrict__ out, float* __restrict__ out_f32,
+                                                     float* __restrict__ tap, const RowMap rm, int d, int T_tree) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x;
+  if (r >= *rm.n_rows) return;
+  float* xr = x + (size_t)r * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float v = xr[c];
+    for (int s = 0; s < S; ++s) v += part[s * pstride + (size_t)r * d + c];
+    if (S > 0) xr[c] = v;
+    ss += v * v;
+  }
+  ss = block_sum(ss, sh);
+  const float sc = 1.0f / sqrtf(ss / (float)d + eps);
+  float* tp = tap ? tap + ((size_t)rm.row_seq[r] * T_tree + rm.row_node[r]) * d : nullptr;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float v = xr[c] * gain[c] * sc;
+    st_f(out + (size_t)r * d + c, v);
+    if (out_f32) out_f32[(size_t)r * d + c] = v;
+    if (tp) tp[c] = v;
+  }
+}
+
+hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
+                              const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s) {
+  if (D.dtype == 0)
+    hipLaunchKernelGGL((k_add_rmsnorm<float>), dim3(rows_max), dim3(256), 0, s, x, part, S, pstride, gain, D.eps, (float*)out,
+                       out_f32, tap, rm, D.d, D.T);
+  else
+    hipLaunchKernelGGL((k_add_rmsnorm<bf16_t>), dim3(rows_max), dim3(256), 0, s, x, part, S, pstride, gain, D.eps,
+                       (bf16_t*)out, out_f32, tap, rm, D.d, D.T);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sum the QKV partials, rotate q and k (pair (j, j + dh/2) by pos * theta^(-2j/dh)), write q for the
+// attention kernel and k, v into the cache at row L + node.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const float* __restrict__ inv_freq,
+                          const RowMap rm, T* __restrict__ q, T* __restrict__ kv_layer, const Dims D) {
+  const int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+  if (r >= *rm.n_rows) return;
+  const int b = rm.row_seq[r], node = rm.row_node[r];
+  const int d = D.d, dh = D.dh, half = dh / 2, N = 3 * d;
+  const int c0 = h * dh + j, c1 = c0 + half;
+  float v[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < S; ++s) {
+    const float* p = part + s * pstride + (size_t)r * N;
+    v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
+  }
+  float sn, cs;
+  sincosf((float)rm.row_pos[r] * inv_freq[j], &sn, &cs);
+  st_f(q + (size_t)r * d + c0, v[0] * cs - v[1] * sn);
+  st_f(q + (size_t)r * d + c1, v[0] * sn + v[1] * cs);
+  const size_t row = (size_t)(rm.seq_L[b] + node);
+  T* Kr = kv_layer + (((size_t)(0 * D.Bmax + b) * D.nH + h) * D.cap + row) * dh;
+  T* Vr = kv_layer + (((size_t)(1 * D.Bmax + b) * D.nH + h) * D.cap + row) * dh;
+  st_f(Kr + j, v[2] * cs - v[3] * sn);
+  st_f(Kr + j + half, v[2] * sn + v[3] * cs);
+  st_f(Vr + j, v[4]);
+  st_f(Vr + j + half, v[5]);
+}
+
+hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
+                          const float* inv_freq, void* q, void* kv_layer, int rows_max, hipStream_t s) {
+  dim3 grid(rows_max, D.nH), block(D.dh / 2);
+  if (D.dtype == 0)
+    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (float*)kv_layer, D);
+  else
+    hipLaunchKernelGGL((k_rope_kv<bf16_t>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (bf16_t*)q,
+                       (bf16_t*)kv_layer, D);
+  return hipGetLastError();
+}
+
+// act = SiLU(gate) * up from the gate/up partials ([.., 2F]: gate columns first)
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, int S, size_t pstride, T* __restrict__ act,
+                                                const RowMap rm, int F, int Fpad) {
+  const int r = blockIdx.x;
+  if (r >= *rm.n_rows) return;
+  const int f = blockIdx.y * 256 + threadIdx.x;
+  if (f >= F) return;
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float* p = part + s * pstride + (size_t)r * 2 * F;
+    g += p[f];
+    u += p[F + f];
+  }
+  st_f(act + (size_t)r * Fpad + f, g / (1.0f + expf(-g)) * u);
+}
+
+hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
+                         int rows_max, hipStream_t s) {
+  dim3 grid(rows_max, (D.F + 255) / 256);
+  if (D.dtype == 0) hipLaunchKernelGGL((k_swiglu<float>), grid, dim3(256), 0, s, part, S, pstride, (float*)act, rm, D.F, D.Fpad);
+  else hipLaunchKernelGGL((k_swiglu<bf16_t>), grid, dim3(256), 0, s, part, S, pstride, (bf16_t*)act, rm, D.F, D.Fpad);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// g[row] = argmax over the vocabulary of the LM-head logits (Algorithm 1 line 9 at every node),
+// lowest id on ties.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_row_argmax(const float* __restrict__ part, int S, size_t pstride, int* __restrict__ g,
+                                                    const cerberus_taps tp, const RowMap rm, int V, int T_tree) {
+  __shared__ float shv[4];
+  __shared__ int shi[4];
+  const int r = blockIdx.x;
+  if (r >= *rm.n_rows) return;
+  const size_t slot = (size_t)rm.row_seq[r] * T_tree + rm.row_node[r];
+  float bv = -INFINITY;
+  int bi = INT_MAX;
+  for (int v = threadIdx.x; v < V; v += 256) {
+    float val = 0.f;
+    for (int s = 0; s < S; ++s) val += part[s * pstride + (size_t)r * V + v];
+    if (tp.logits) tp.logits[slot * V + v] = val;
+    better(bv, bi, val, v);
+  }
+  block_argmax(bv, bi, shv, shi);
+  if (threadIdx.x == 0) {
+    int best = bi == INT_MAX ? 0 : bi;
+    if (tp.node_argmax) tp.node_argmax[slot] = best;
+    if (tp.forced_node_argmax) best = tp.forced_node_argmax[slot];
+    g[r] = best;
+  }
+}
+
+hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, int* g,
+                             const cerberus_taps& tp, int rows_max, hipStream_t s) {
+  hipLaunchKernelGGL(k_row_argmax, dim3(rows_max), dim3(256), 0, s, part, S, pstride, g, tp, rm, D.V, D.T);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Acceptance (tree verification's outcome): walk down from the root while a child carries the
+// token the base model itself produced at the current node; lowest child index on duplicates.
+// One thread per sequence; the walk is at most Hc steps over at most 64 nodes.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_accept(const Dims D, const TreeDev tr, const RowMap rm, const int* __restrict__ g,
+                                               const int* __restrict__ tok, const cerberus_state st, int* __restrict__ path,
+                                               int* __restrict__ last_row, int batch) {
+  const int b = threadIdx.x;
+  if (b >= batch) return;
+  const int Tb = rm.seq_T[b];
+  if (Tb <= 0) { st.accept_len[b] = 0; last_row[b] = -1; return; }
+  const int row0 = rm.seq_row0[b], W = D.Hc + 1;
+  int cur = 0, a = 1;
+  path[b * W] = 0;
+  while (a < W) {
+    const int want = g[row0 + cur];
+    int nxt = -1;
+    for (int c = cur + 1; c < Tb; ++c)
+      if (tr.parent[c] == cur && tok[row0 + c] == want) { nxt = c; break; }
+    if (nxt < 0) break;
+    path[b * W + a] = nxt;
+    ++a;
+    cur = nxt;
+  }
+  for (int j = 0; j < a; ++j) {
+    st.accepted_nodes[b * W + j] = path[b * W + j];
+    st.accepted_tokens[b * W + j] = tok[row0 + path[b * W + j]];
+  }
+  st.accept_len[b] = a;
+  st.root_token[b] = g[row0 + cur];
+  st.kv_len[b] = rm.seq_L[b] + a;
+  last_row[b] = row0 + cur;
+}
+
+hipError_t launch_accept(const Dims& D, const TreeDev& tr, const RowMap& rm, const int* g, const int* tok,
+                         const cerberus_state& st, int* path, int* last_row, int batch, hipStream_t s) {
+  hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, s, D, tr, rm, g, tok, st, path, last_row, batch);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// KV compaction: cache row L + path[j] -> row L + j for j = 1..a-1, in every layer, K and V, head.
+// A thread owns one 16-byte column piece of a (layer, K|V, head) slice: it loads the pieces of all
+// source rows (j ascending) and only then stores them.  Row L + j can only be the source of a copy
+// j' <= j, whose load was issued no later than load j, and loads return in order, so every store
+// follows all loads of the row it overwrites; different threads touch disjoint bytes.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_compact(const Dims D, const RowMap rm, const cerberus_state st,
+                                                const int* __restrict__ path, int elem_bytes) {
+  const int lk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int a = st.accept_len[b];
+  if (a <= 1) return;
+  const int pieces = D.dh * elem_bytes / 16;
+  const int t = threadIdx.x;
+  if (t >= pieces) return;
+  const int L = rm.seq_L[b], W = D.Hc + 1;
+  const size_t row_bytes = (size_t)D.dh * elem_bytes;
+  unsigned char* base = reinterpret_cast<unsigned char*>(st.kv) + (((size_t)lk * D.Bmax + b) * D.nH + h) * D.cap * row_bytes;
+  uint4 regs[CERBERUS_MAX_HEADS];
+#pragma unroll
+  for (int j = 1; j <= CERBERUS_MAX_HEADS; ++j)
+    if (j < a) regs[j - 1] = reinterpret_cast<const uint4*>(base + (size_t)(L + path[b * W + j]) * row_bytes)[t];
+#pragma unroll
+  for (int j = 1; j <= CERBERUS_MAX_HEADS; ++j)
+    if (j < a) reinterpret_cast<uint4*>(base + (size_t)(L + j) * row_bytes)[t] = regs[j - 1];
+}
+
+hipError_t launch_compact(const Dims& D, const RowMap& rm, const cerberus_state& st, const int* path, int batch,
+                          hipStream_t s) {
+  hipLaunchKernelGGL(k_compact, dim3(D.n_layers * 2, D.nH, batch), dim3(64), 0, s, D, rm, st, path, D.dtype == 0 ? 4 : 2);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Entropy gate (Section 4.2): P = softmax(h) over the d components of one hidden vector,
+// S = -sum P log2 P = (ln Z - sum_i e_i z_i / Z) / ln 2 with z = h - max h, e = exp(z), Z = sum e.
+// flag = 1 (auto-regressive) iff S > T; equality and only equality-or-below keeps the parallel
+// path, and a NaN entropy takes the auto-regressive one.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_gate(int d, float threshold, const float* __restrict__ base,
+                                              const int* __restrict__ row_index, const float* __restrict__ forced,
+                                              const int* __restrict__ seq_T, float* __restrict__ entropy, int* __restrict__ flag) {
+  __shared__ float shf[4];
+  __shared__ double shd[4];
+  const int r = blockIdx.x;
+  if (seq_T && seq_T[r] <= 0) return;
+  const float* h = forced ? forced + (size_t)r * d : base + (size_t)(row_index ? row_index[r] : r) * d;
+  float m = -INFINITY;
+  bool bad = false;
+  for (int c = threadIdx.x; c < d; c += 256) { m = fmaxf(m, h[c]); bad = bad || (h[c] != h[c]); }
+  m = block_max(m, shf);
+  double Z = 0.0, A = 0.0;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float z = h[c] - m;
+    const float e = expf(z);
+    Z += (double)e;
+    if (e > 0.f) A += (double)e * (double)z;
+  }
+  Z = block_sum(Z, shd);
+  A = block_sum(A, shd);
+  const double nbad = block_sum(bad ? 1.0 : 0.0, shd);
+  if (threadIdx.x == 0) {
+    double S = (log(Z) - A / Z) / 0.6931471805599453;
+    if (nbad > 0.0) S = NAN;
+    entropy[r] = (float)S;
+    flag[r] = (S <= (double)threshold) ? 0 : 1;
+  }
+}
+
+hipError_t launch_gate(int d, float threshold, const float* base, const int* row_index, const float* forced,
+                       const int* seq_T, int rows, float* entropy, int* flag, hipStream_t s) {
+  hipLaunchKernelGGL(k_gate, dim3(rows), dim3(256), 0, s, d, threshold, base, row_index, forced, seq_T, entropy, flag);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Cerberus heads (Section 4.1).  State of head i before stage s lives in hsF/hsA[s & 1][i][b][0..w);
+// where the coming stage is the special block, [d..2d) of head i holds head i-1's state, so the
+// stage's GEMM simply sees the concatenation (own state first).
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_heads_prepare(const Dims D, const float* __restrict__ h_last,
+                                                       const int* __restrict__ last_row, float* __restrict__ hsF,
+                                                       T* __restrict__ hsA) {
+  const int b = blockIdx.x;
+  const int lr = last_row[b];
+  const int d = D.d, ld = 2 * d;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    const float v = lr >= 0 ? h_last[(size_t)lr * d + c] : 0.f;
+    for (int i = 0; i < D.Hc; ++i) {
+      const size_t o = ((size_t)i * 16 + b) * ld + c;
+      hsF[o] = v;
+      st_f(hsA + o, v);
+      if (D.sb == 0 && i >= 1) { hsF[o + d] = v; st_f(hsA + o + d, v); }
+    }
+  }
+}
+
+hipError_t launch_heads_prepare(const Dims& D, const float* h_last, const int* last_row, float* hsF, void* hsA, int batch,
+                                hipStream_t s) {
+  if (D.dtype == 0) hipLaunchKernelGGL((k_heads_prepare<float>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (float*)hsA);
+  else hipLaunchKernelGGL((k_heads_prepare<bf16_t>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (bf16_t*)hsA);
+  return hipGetLastError();
+}
+
+// Resblock tail: Output = SiLU((W h + b) + h) from the GEMM partials of W h (Section 4.1).
+template <typename T>
+__global__ __launch_bounds__(256) void k_resblock_finish(const ResFinishArgs a, const float* __restrict__ curF,
+                                                         float* __restrict__ nxtF, T* __restrict__ nxtA, int d, int Hc,
+                                                         int link_next) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  const int col = blockIdx.z * 256 + threadIdx.x;
+  const int w = a.width[i], ld = 2 * d;
+  if (col >= w) return;
+  const size_t o = ((size_t)i * 16 + b) * ld + col;
+  float v = a.bias[i][col] + curF[o];
+  for (int s = 0; s < a.S[i]; ++s) v += a.part[i][s * a.pstride[i] + (size_t)b * w + col];
+  v = v / (1.0f + expf(-v));
+  nxtF[o] = v;
+  st_f(nxtA + o, v);
+  if (link_next && i + 1 < Hc && col < d) {
+    const size_t o2 = ((size_t)(i + 1) * 16 + b) * ld + d + col;
+    nxtF[o2] = v;
+    st_f(nxtA + o2, v);
+  }
+}
+
+hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const float* curF, float* nxtF, void* nxtA,
+                                  int link_next, int batch, hipStream_t s) {
+  dim3 grid(D.Hc, batch, (2 * D.d + 255) / 256);
+  if (D.dtype == 0)
+    hipLaunchKernelGGL((k_resblock_finish<float>), grid, dim3(256), 0, s, a, curF, nxtF, (float*)nxtA, D.d, D.Hc, link_next);
+  else
+    hipLaunchKernelGGL((k_resblock_finish<bf16_t>), grid, dim3(256), 0, s, a, curF, nxtF, (bf16_t*)nxtA, D.d, D.Hc, link_next);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per-head top-k (the heads' token candidates): k rounds of a block-wide argmax, each round
+// restricted to entries that come strictly after the previous winner in the order
+// (value descending, id ascending).  Sequences whose gate chose the auto-regressive step keep
+// their old candidates.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_topk(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
+                                              int topk) {
+  __shared__ float shv[4];
+  __shared__ int shi[4];
+  const int i = blockIdx.x, b = blockIdx.y;
+  if (st.gate_flag[b] != 0 || a.seq_T[b] <= 0) return;
+  const float* lg = a.logits[i] + (size_t)b * V;
+  if (tp.head_logits)
+    for (int v = threadIdx.x; v < V; v += 256) tp.head_logits[((size_t)b * Hc + i) * V + v] = lg[v];
+  float pv = INFINITY;
+  int pi = -1;
+  for (int k = 0; k < topk; ++k) {
+    float bv = -INFINITY;
+    int bi = INT_MAX;
+    for (int v = threadIdx.x; v < V; v += 256) {
+      const float val = lg[v];
+      if (val < pv || (val == pv && v > pi)) better(bv, bi, val, v);
+    }
+    block_argmax(bv, bi, shv, shi);
+    if (bi == INT_MAX) bi = 0;
+    if (threadIdx.x == 0) st.cand[((size_t)b * Hc + i) * topk + k] = bi;
+    pv = bv;
+    pi = bi;
+  }
+}
+
+hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& st, const cerberus_taps& tp, int batch,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(k_topk, dim3(D.Hc, batch), dim3(256), 0, s, a, st, tp, D.V, D.Hc, D.topk);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// init-time helpers
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_to_f32(const T* __restrict__ in, float* __restrict__ out, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = ld_f(in + i);
+}
+
+hipError_t launch_to_f32(const void* in, float* out, int n, int dtype, hipStream_t s) {
+  if (dtype == 0) hipLaunchKernelGGL((k_to_f32<float>), dim3((n + 255) / 256), dim3(256), 0, s, (const float*)in, out, n);
+  else hipLaunchKernelGGL((k_to_f32<bf16_t>), dim3((n + 255) / 256), dim3(256), 0, s, (const bf16_t*)in, out, n);
+  return hipGetLastError();
+}
+
+}  // namespace cerb
