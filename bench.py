@@ -1,0 +1,230 @@
+"""Benchmark of the Cerberus verify step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|13b|tiny] [--no-graph] [--no-cpu]
+
+A step is one full pass of the hot path over one batch: tree assembly, 32 decoder layers over the
+64-node tree with tree-masked attention against a 1024-row KV prefix, LM head and per-node argmax,
+acceptance, KV compaction, entropy gate, Cerberus heads and top-k (gate forced to the parallel path,
+so the heads always run).  Weights, KV prefix and candidates are synthetic (seeded, random-init) and
+resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+GEMM_KINDS = ["qkv", "attn_out", "ffn_gate_up", "ffn_down", "lm_head", "head_resblocks", "head_fc"]
+
+
+def algorithmic_bytes(cfg: dict, T: int, L: int, elem: int = 2) -> dict:
+    """Bytes one step must move when every weight and every live KV row is read once."""
+    d, F, V, NL, Hc = cfg["d_model"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"], cfg["n_cerb_heads"]
+    from paper_2410_13344_amd import synth
+    layer_w = (3 * d * d + d * d + 2 * F * d + d * F) * elem
+    heads = 0
+    for i, widths in enumerate(synth.head_block_widths(cfg)):
+        heads += sum(w * w + w for w in widths) * elem + V * widths[-1] * elem
+    out = {
+        "layer_weights": NL * layer_w,
+        "lm_head": V * d * elem,
+        "kv_prefix_read": NL * 2 * L * d * elem,
+        "tree_kv_write_read": NL * 2 * T * d * elem * 2,
+        "heads": heads,
+        "embedding_rows": T * d * elem,
+    }
+    out["total"] = sum(out.values())
+    return out
+
+
+def cpu_baseline(cfg: dict, W_dev: dict, parent, rank, L: int, cap: int, n_sample_layers: int = 2) -> dict:
+    """Times the CPU oracle, as it stands, on a bounded sample of the same workload: the full
+    step (all tree nodes, LM head, gate, heads, top-k) with `n_sample_layers` of the decoder layers,
+    then scales the per-layer part to the full depth."""
+    import numpy as np
+    import torch
+    from oracle import cerberus_oracle as orc
+    from paper_2410_13344_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+
+    sub = dict(cfg, n_layers=n_sample_layers)
+    W = {k: synth.to_host_f32(v) for k, v in W_dev.items() if k != "layers"}
+    W["layers"] = [synth.to_host_f32(W_dev["layers"][l]) for l in range(n_sample_layers)]
+    kv_t = synth.make_kv_prefix(sub, 1, cap, seed=0, dtype=torch.bfloat16, device="cpu")
+    kv = [(kv_t[l, 0, 0].double().numpy(), kv_t[l, 1, 0].double().numpy()) for l in range(n_sample_layers)]
+    root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    cand = synth.make_candidates(cfg, 1, seed=3)[0].numpy()
+
+    def run(n_layers_used):
+        c = dict(sub, n_layers=n_layers_used)
+        st = orc.new_state([(K.copy(), V.copy()) for K, V in kv[:max(n_layers_used, 1)]], L, root, cand, 0)
+        t0 = time.perf_counter()
+        orc.verify_step(c, W, parent, rank, st)
+        return time.perf_counter() - t0
+
+    t_full = run(n_sample_layers)
+    t_rest = run(0)                       # embedding, LM head, gate, heads, top-k only
+    per_layer = max(t_full - t_rest, 0.0) / n_sample_layers
+    est = t_rest + per_layer * cfg["n_layers"]
+    return {"value": est * 1e6, "unit": "us/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"full step with {n_sample_layers} of {cfg['n_layers']} decoder layers timed "
+                      f"({t_full:.2f} s) and without layers ({t_rest:.2f} s); per-layer time scaled to "
+                      f"{cfg['n_layers']} layers",
+            "measured_s": round(t_full + t_rest, 3)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="7b", choices=["7b", "13b", "tiny"])
+    ap.add_argument("--prefix", type=int, default=None)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--param", action="append", default=[], help="library tuning knob name=value")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path has no inter-GPU part); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2410_13344_amd import binding as B
+    from paper_2410_13344_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2410_13344_amd.build import build_library
+        build_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    name = args.workload
+    cfg = synth.make_config(name)                      # entropy_threshold = +inf: gate forced parallel
+    tree_name = "tiny" if name == "tiny" else "p63"
+    L = args.prefix if args.prefix is not None else {"7b": 1024, "13b": 2048, "tiny": 128}[name]
+    parent, rank = synth.make_tree(tree_name, cfg["n_cerb_heads"])
+    T = len(parent)
+    cap = ((L + T + 127) // 128 + 1) * 128
+    dtype = B.CERBERUS_BF16
+    W = synth.make_weights(cfg, seed=0, dtype=torch.bfloat16, device="cuda")
+    eng = B.Engine(cfg, W, parent, rank, dtype, 1, cap)
+    for kv in args.param:
+        k, v = kv.split("=")
+        eng.set_param(k, int(v))
+    st = eng.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
+    st.root_token[0] = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    st.cand[0] = synth.make_candidates(cfg, 1, seed=3)[0].cuda()
+    st.gate_flag[0] = 0
+    L_dev = torch.full((1,), L, dtype=torch.int32, device="cuda")
+
+    def step():
+        st.kv_len.copy_(L_dev)          # every repetition sees the configured prefix length
+        eng.verify_step(st, 1)
+
+    graph = None
+    if not args.no_graph:
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            for _ in range(2):
+                step()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+    run = graph.replay if graph is not None else step
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    accepted = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) / args.steps * 1e3
+    accepted = int(st.accept_len[0]) * args.steps
+    assert int(st.status[0]) == 0, "device status word set"
+
+    # per-step distribution from events (separate pass)
+    n_ev = min(args.steps, 50)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for a, b in evs:
+        a.record()
+        run()
+        b.record()
+    torch.cuda.synchronize()
+    lat = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
+
+    # dominant kernel: the weight-streaming GEMM.  Every kind is replayed back to back over all
+    # layers (fresh weights each launch, so no cache reuse) between two events on this stream.
+    gemm = {}
+    tot_bytes = tot_ms = 0.0
+    n_launch = 0
+    for kind, kname in enumerate(GEMM_KINDS):
+        rows = 1 if kind >= 5 else T
+        reps = 3 if kind <= 3 else 20
+        B.cerberus_bench_gemm(eng.ctx, kind, rows)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            nbytes = B.cerberus_bench_gemm(eng.ctx, kind, rows)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        launches = cfg["n_layers"] if kind <= 3 else (cfg["n_resblocks"] if kind == 5 else 1)
+        gemm[kname] = {"ms_per_step": round(ms, 4), "launches": launches, "GB": round(nbytes / 1e9, 4),
+                       "GBps": round(nbytes / ms / 1e6, 1), "us_per_launch": round(ms * 1e3 / launches, 2)}
+        if kind <= 4:     # the MT=4 kernel instance (tree rows); head GEMMs run the 16-row instance
+            tot_bytes += nbytes
+            tot_ms += ms
+            n_launch += launches
+    achieved = tot_bytes / tot_ms / 1e6
+    alg = algorithmic_bytes(cfg, T, L)
+
+    out = {
+        "metric": "verify_step_latency", "value": round(ms_per_step * 1e3, 1), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{name}-shape bf16, {T}-node tree, KV prefix {L}, batch 1, gate forced parallel",
+                   "graph": graph is not None},
+        "latency_us": {"p10": round(float(np.percentile(lat, 10)), 1), "p50": round(float(np.percentile(lat, 50)), 1),
+                       "p90": round(float(np.percentile(lat, 90)), 1)},
+        "tokens_per_s": round(accepted / (t1 - t0), 2),
+        "step_algorithmic_GB": round(alg["total"] / 1e9, 4),
+        "step_hbm_frac": round(alg["total"] / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
+        "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2> (QKV, O, gate/up, down, LM head)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_launch_us": round(tot_ms * 1e3 / n_launch, 2), "launches_per_step": n_launch,
+                     "per_kind": gemm},
+    }
+    if not args.no_cpu and name != "tiny":
+        out["cpu_baseline"] = cpu_baseline(cfg, W, parent, rank, L, cap)
+    elif not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, W, parent, rank, L, cap, n_sample_layers=cfg["n_layers"])
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

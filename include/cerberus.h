@@ -73,9 +73,9 @@ typedef struct {
 } cerberus_config;
 
 /* Weights, all DEVICE, element type per `dtype`, row-major [out][in].  The pointer arrays
- * themselves are HOST arrays.  cerberus_init repacks the matrices into the workspace; after it
- * returns the library reads `embed` and the norm gains / biases from the caller's buffers, so
- * those must stay alive; the matrices may be freed.                                          */
+ * themselves are HOST arrays.  In bf16 mode cerberus_init repacks the matrices into the
+ * workspace and copies gains and biases, so after it returns only `embed` must stay alive; in
+ * fp32 mode the matrices are read in place and must all stay alive.                           */
 typedef struct {
   const void *embed;            /* [vocab][d]                                                */
   const void *final_norm;       /* [d]                                                       */
@@ -162,6 +162,13 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
 
 /* Tuning knobs, by name; returns CERBERUS_ERR_ARG for an unknown name or a bad value.          */
 int cerberus_set_param(cerberus_ctx *ctx, const char *name, int32_t value);
+
+/* Benchmark hook: enqueues back to back, for every layer (or head stage), the GEMM launches of
+ * one kind exactly as a step launches them for `rows` rows, reading whatever the activation
+ * buffers hold; results land in scratch.  kind: 0 QKV, 1 attention output, 2 FFN gate/up,
+ * 3 FFN down, 4 LM head, 5 head Resblocks (all stages), 6 head FC.  Writes to *bytes (HOST, may
+ * be NULL) the weight + activation bytes the launches read once each.                          */
+int cerberus_bench_gemm(cerberus_ctx *ctx, int32_t kind, int32_t rows, void *stream, double *bytes);
 
 /* Text of the last error raised on this thread (never NULL).                                   */
 const char *cerberus_last_error(void);

@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         L.cerberus_set_taps.argtypes = [C.c_void_p, C.POINTER(Taps)]
         L.cerberus_set_param.restype = C.c_int
         L.cerberus_set_param.argtypes = [C.c_void_p, C.c_char_p, C.c_int32]
+        L.cerberus_bench_gemm.restype = C.c_int
+        L.cerberus_bench_gemm.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
         L.cerberus_last_error.restype = C.c_char_p
         L.cerberus_last_error.argtypes = []
         L.cerberus_destroy.restype = None
@@ -186,6 +188,12 @@ def cerberus_set_taps(ctx: int, taps: Optional[Taps]) -> None:
 
 def cerberus_set_param(ctx: int, name: str, value: int) -> None:
     _check(lib().cerberus_set_param(ctx, name.encode(), value))
+
+
+def cerberus_bench_gemm(ctx: int, kind: int, rows: int, stream=None) -> float:
+    nbytes = C.c_double(0.0)
+    _check(lib().cerberus_bench_gemm(ctx, kind, rows, _stream_ptr(stream), C.byref(nbytes)))
+    return nbytes.value
 
 
 def cerberus_destroy(ctx: int) -> None:

@@ -102,6 +102,7 @@ int validate(const cerberus_config* c, const cerberus_tree* t) {
   if (c->head_dim != 64 && c->head_dim != 128) return fail(CERBERUS_ERR_SHAPE, "head_dim must be 64 or 128");
   if (c->d_model != c->n_heads * c->head_dim) return fail(CERBERUS_ERR_SHAPE, "d_model != n_heads * head_dim");
   if (c->d_ffn % 8 || c->vocab % 16) return fail(CERBERUS_ERR_SHAPE, "d_ffn must be a multiple of 8 and vocab of 16");
+  if (c->dtype == CERBERUS_BF16 && c->d_model % 256) return fail(CERBERUS_ERR_SHAPE, "bf16 mode needs d_model to be a multiple of 256");
   if (c->n_cerb_heads < 1 || c->n_cerb_heads > CERBERUS_MAX_HEADS) return fail(CERBERUS_ERR_SHAPE, "n_cerb_heads out of 1..%d", CERBERUS_MAX_HEADS);
   if (c->n_resblocks < 1 || c->n_resblocks > 16) return fail(CERBERUS_ERR_SHAPE, "n_resblocks out of 1..16");
   if (c->special_block >= c->n_resblocks) return fail(CERBERUS_ERR_SHAPE, "special_block >= n_resblocks");
@@ -510,6 +511,33 @@ int cerberus_accept(cerberus_ctx* ctx, const int32_t* node_argmax, const int32_t
   HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, s));
   HIP_TRY(launch_accept(ctx->D, ctx->tree, ctx->rm, node_argmax, node_token, *st, ctx->path, ctx->last_row, batch, s));
   HIP_TRY(launch_compact(ctx->D, ctx->rm, *st, ctx->path, batch, s));
+  return CERBERUS_OK;
+}
+
+int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* stream, double* bytes) {
+  if (!ctx) return fail(CERBERUS_ERR_ARG, "null context");
+  const Dims& D = ctx->D;
+  const bool head_kind = kind == 5 || kind == 6;
+  if (kind < 0 || kind > 6) return fail(CERBERUS_ERR_ARG, "kind out of 0..6");
+  if (rows < 1 || rows > (head_kind ? D.Bmax : D.Bmax * D.T)) return fail(CERBERUS_ERR_ARG, "rows out of range");
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  double total = 0.0;
+  auto run = [&](const GemmBatch& g) -> int {
+    for (int p = 0; p < g.n_prob; ++p)
+      total += ((double)g.p[p].N * g.p[p].K + (double)rows * g.p[p].K) * ctx->elem;
+    return run_gemm(ctx, g, nullptr, rows, rows, nullptr, 0, s);
+  };
+  if (kind <= 3) {
+    const std::vector<GemmBatch>& v = kind == 0 ? ctx->p_qkv : kind == 1 ? ctx->p_o : kind == 2 ? ctx->p_gu : ctx->p_down;
+    for (int l = 0; l < D.n_layers; ++l) TRY(run(v[l]));
+  } else if (kind == 4) {
+    TRY(run(ctx->p_lm));
+  } else if (kind == 5) {
+    for (int st_i = 0; st_i < D.R; ++st_i) TRY(run(ctx->p_res[st_i]));
+  } else {
+    TRY(run(ctx->p_fc));
+  }
+  if (bytes) *bytes = total;
   return CERBERUS_OK;
 }
 

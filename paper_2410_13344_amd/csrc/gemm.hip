@@ -41,11 +41,11 @@ hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int K
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA GEMM.  Workgroup = 4 waves; wave w owns NSUB adjacent 16-column slabs; a workgroup
 // covers 64*NSUB columns, MT*16 rows and one split of K (whole chunks of 256 k).  A is staged
-// through a double-buffered LDS tile per chunk (row stride 528 B: the 16 lanes of an MFMA row
-// group then hit 64 distinct banks); the main loop has no branches, so the weight loads stay in
-// flight across chunk boundaries.
+// through a double-buffered LDS tile per chunk (512 B rows, 16-byte pieces XOR-swizzled by the row
+// index so the 16 lanes of an MFMA row group hit 64 distinct banks); the main loop has no
+// branches, so the weight loads stay in flight across chunk boundaries.
 // ---------------------------------------------------------------------------------------------
-constexpr int kLdsRow = 528;   // 256 bf16 + 16 B pad
+constexpr int kLdsRow = 512;   // 256 bf16, pieces swizzled
 constexpr int kRing = 4;       // k-steps of weights in flight per wave
 
 __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
     for (int i = 0; i < kApt; ++i) {
       const int idx = threadIdx.x + i * 256;
       const int r = idx >> 5, pc = idx & 31;
-      *reinterpret_cast<uint4*>(lds + buf * kBuf + r * kLdsRow + pc * 16) = areg[i];
+      *reinterpret_cast<uint4*>(lds + buf * kBuf + r * kLdsRow + ((pc ^ (r & 15)) * 16)) = areg[i];
     }
   };
 
@@ -126,10 +126,10 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   store_a(0);
   __syncthreads();
 
-  const int a_off = (lane & 15) * kLdsRow + (lane >> 4) * 16;
+  const int a_row = lane & 15, a_grp = lane >> 4;  // (mt*16 + a_row) & 15 == a_row
   for (int c = 0; c < nchunks; ++c) {
     load_a(min(c + 1, nchunks - 1));
-    const unsigned char* L = lds + (c & 1) * kBuf + a_off;
+    const unsigned char* L = lds + (c & 1) * kBuf + a_row * kLdsRow;
     const int kb = ks0 + c * 8;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
       }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + s * 64);
+        const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((s * 4 + a_grp) ^ a_row) * 16));
 #pragma unroll
         for (int j = 0; j < NSUB; ++j)
           acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),

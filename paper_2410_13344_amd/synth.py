@@ -246,17 +246,20 @@ class LazyHostLayers:
     """Sequence view over W["layers"] that converts one layer to host float32 on access,
     so a 7B-shaped model never has to sit in host memory as a whole."""
 
-    def __init__(self, layers):
+    def __init__(self, layers, on_access=None):
         self._layers = layers
+        self._on_access = on_access
 
     def __len__(self):
         return len(self._layers)
 
     def __getitem__(self, l):
+        if self._on_access is not None:
+            self._on_access(l)
         return to_host_f32(self._layers[l])
 
 
-def to_host_lazy(W: dict) -> dict:
+def to_host_lazy(W: dict, on_access=None) -> dict:
     out = {k: to_host_f32(v) for k, v in W.items() if k != "layers"}
-    out["layers"] = LazyHostLayers(W["layers"])
+    out["layers"] = LazyHostLayers(W["layers"], on_access)
     return out

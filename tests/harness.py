@@ -24,7 +24,7 @@ class Tol:
     kv_rtol: float
 
 
-TOL_F32 = Tol(logits=2e-3, hidden=1e-3, entropy=1e-3, kv_atol=1e-3, kv_rtol=1e-3)
+TOL_F32 = Tol(logits=5e-5, hidden=5e-5, entropy=1e-5, kv_atol=2e-5, kv_rtol=2e-5)
 # bf16 GPU vs float64 oracle: 2e-2 max-abs on logits is the bar of the benchmark spec
 TOL_BF16 = Tol(logits=2e-2, hidden=3e-2, entropy=3e-2, kv_atol=3e-2, kv_rtol=2e-2)
 
@@ -113,20 +113,24 @@ def compare_step(cfg: dict, out: dict, st: B.DeviceState, taps: B.DeviceTaps, b:
     if not np.array_equal(g_gpu[safe], g_orc[safe]):
         bad(f"per-node argmax differs at nodes {np.nonzero(safe & (g_gpu != g_orc))[0].tolist()}")
 
-    # acceptance: exact whenever every decision on the oracle's path was clear-cut
+    # acceptance: exact whenever every decision on the oracle's path was clear-cut; when one was a
+    # near-tie the device may legitimately take another path, and the rest of the step (which
+    # depends on the path) is compared only if it took the same one
     path = out["path"]
-    if forced_argmax or all(safe[n] for n in path):
+    a = int(st.accept_len[b])
+    nodes = st.accepted_nodes[b, :a].cpu().numpy().tolist()
+    clear = forced_argmax or all(safe[n] for n in path)
+    same = (a == out["accept_len"] and nodes == list(path))
+    if clear and not same:
+        bad(f"accepted path {nodes} (len {a}) vs oracle {list(path)}")
+    if same:
         rep.accept_checked = True
-        a = int(st.accept_len[b])
-        W = Hc + 1
-        nodes = st.accepted_nodes[b, :a].cpu().numpy().tolist()
         toks = st.accepted_tokens[b, :a].cpu().numpy().tolist()
-        if a != out["accept_len"] or nodes != list(path):
-            bad(f"accepted path {nodes} (len {a}) vs oracle {list(path)}")
-        elif toks != [int(t) for t in out["committed"]]:
+        if toks != [int(t) for t in out["committed"]]:
             bad(f"committed tokens {toks} vs {out['committed'].tolist()}")
-        if int(st.root_token[b]) != out["root"]:
-            bad(f"next root {int(st.root_token[b])} vs {out['root']}")
+        if safe[path[-1]] or forced_argmax:
+            if int(st.root_token[b]) != out["root"]:
+                bad(f"next root {int(st.root_token[b])} vs {out['root']}")
         if int(st.kv_len[b]) != out["L_after"]:
             bad(f"kv_len {int(st.kv_len[b])} vs {out['L_after']}")
         # compacted cache rows of this step

@@ -218,3 +218,107 @@ def test_bad_arguments_are_rejected(tiny_pairs):
         pair.engine.verify_step(st, 2)               # batch > max_batch
     with pytest.raises(B.CerberusError):
         pair.engine.set_param("no_such_knob", 1)
+
+
+# ---------------------------------------------------------------------------------------------
+# full size: the 7B shape in the launch configuration bench.py times (bf16, 64-node tree, prefix
+# 1024).  The oracle cannot afford all 64 nodes, so it runs one sampled root-to-leaf path as a chain
+# tree: a node's result depends only on the prefix and its ancestors, so the chain's rows must equal
+# the corresponding rows of the full tree pass.
+# ---------------------------------------------------------------------------------------------
+def test_7b_full_size_sampled_path_matches_oracle():
+    L, cap = 1024, 1280
+    say("7B: building weights and engine")
+    pair = H.Pair("7b", BF16, "p63", seed=0, max_batch=1, kv_capacity=cap, lazy_host=True)
+    cfg, T, tol = pair.cfg, pair.T, H.TOL_BF16
+    assert T == 64
+    st = pair.engine.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
+    root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    cand = synth.make_candidates(cfg, 1, seed=3)[0]
+    st.kv_len[0], st.root_token[0], st.gate_flag[0] = L, root, 0
+    st.cand[0] = cand.cuda()
+
+    # sampled path: the deepest leaf with the largest index
+    depth, _ = orc.tree_tables(pair.parent)
+    leaf = max(n for n in range(T) if depth[n] == cfg["n_cerb_heads"])
+    nodes = []
+    n = leaf
+    while n >= 0:
+        nodes.append(n)
+        n = pair.parent[n]
+    nodes.reverse()
+    chain_parent = [-1] + list(range(len(nodes) - 1))
+    chain_rank = [pair.rank[n] for n in nodes]
+
+    # force the acceptance down that path on both sides, so that a depth-4 commit and its
+    # compaction are exercised at full size; 777 is the (forced) next root
+    taps = pair.taps(forced_argmax=True)
+    forced_full = torch.full((T,), -1, dtype=torch.int32)
+    tok_full = orc.tree_tokens(root, cand.numpy(), pair.parent, pair.rank)
+    forced_chain = np.zeros(len(nodes), dtype=np.int64)
+    for j, n in enumerate(nodes):
+        nxt = tok_full[nodes[j + 1]] if j + 1 < len(nodes) else 777
+        forced_full[n] = int(nxt)
+        forced_chain[j] = int(nxt)
+    taps.forced_node_argmax.copy_(forced_full.cuda())
+
+    kv_before = st.kv.clone()
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    say("7B: device step done; running the oracle on the sampled chain " + str(nodes))
+
+    kv_host = [(kv_before[l, 0, 0].double().cpu().numpy(), kv_before[l, 1, 0].double().cpu().numpy())
+               for l in range(cfg["n_layers"])]
+    W_lazy = pair.W
+    W_lazy["layers"]._on_access = lambda l: say(f"  oracle layer {l}") if l % 4 == 0 else None
+    ost = orc.new_state(kv_host, L, root, cand.numpy(), 0)
+    out = orc.verify_step(cfg, W_lazy, chain_parent, chain_rank, ost, forced_node_argmax=forced_chain)
+    assert out["path"] == list(range(len(nodes))) and out["accept_len"] == len(nodes)
+
+    idx = torch.tensor(nodes)
+    assert np.array_equal(taps.node_token[idx].cpu().numpy(), out["tok"])
+    logits = taps.logits[idx].double().cpu().numpy()
+    err = float(np.max(np.abs(logits - out["logits"])))
+    herr = float(np.max(np.abs(taps.h_last[idx].double().cpu().numpy() - out["h_last"])))
+    say(f"7B: logits max-abs err {err:.3e} (std of logits {out['logits'].std():.3f}), h_last err {herr:.3e}")
+    assert err <= tol.logits
+    srt = -np.sort(-out["logits"], axis=1)
+    safe = (srt[:, 0] - srt[:, 1]) > 2 * tol.logits
+    g_real = np.argmax(out["logits"], axis=1)
+    assert np.array_equal(taps.node_argmax[idx].cpu().numpy()[safe], g_real[safe])
+    say(f"7B: argmax checked on {int(safe.sum())}/{len(nodes)} nodes")
+
+    a = int(st.accept_len[0])
+    assert a == len(nodes)
+    assert st.accepted_nodes[0, :a].cpu().tolist() == nodes
+    assert st.accepted_tokens[0, :a].cpu().tolist() == [int(t) for t in out["committed"]]
+    assert int(st.root_token[0]) == 777 and int(st.kv_len[0]) == L + a
+    # compaction: rows L..L+a-1 now hold the accepted nodes' K/V (the oracle's chain wrote them there
+    # directly); the copy itself is checked bit for bit in test_accept_entry_point_is_bit_exact
+    for l in (0, 13, cfg["n_layers"] - 1):
+        for kvi in (0, 1):
+            got = st.kv[l, kvi, 0, :, L:L + a].double().cpu().numpy()
+            want = ost["kv"][l][kvi][:, L:L + a]
+            assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, np.max(np.abs(got - want)))
+    assert torch.equal(st.kv[:, :, :, :, :L], kv_before[:, :, :, :, :L])
+
+    S_gpu = float(st.entropy[0])
+    say(f"7B: entropy {S_gpu:.5f} vs {out['entropy']:.5f}")
+    assert abs(S_gpu - out["entropy"]) <= tol.entropy and int(st.gate_flag[0]) == 0
+    hl = taps.head_logits[0].double().cpu().numpy()
+    want = np.stack(out["head_logits"])
+    herr2 = float(np.max(np.abs(hl - want)))
+    say(f"7B: head logits max-abs err {herr2:.3e} (std {want.std():.3f})")
+    assert herr2 <= tol.logits
+    K = cfg["topk"]
+    cand_gpu = st.cand[0].cpu().numpy()
+    checked = 0
+    for i in range(cfg["n_cerb_heads"]):
+        s = -np.sort(-want[i])[:K + 1]
+        for j in range(K):
+            if H._margin_ok(s, j, tol.logits):
+                checked += 1
+                assert cand_gpu[i, j] == out["cand"][i, j], (i, j)
+    say(f"7B: candidates checked {checked}/{cfg['n_cerb_heads'] * K}")
