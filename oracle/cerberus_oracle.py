@@ -110,12 +110,18 @@ def new_kv(cfg: dict, capacity: int) -> list:
 
 
 def decoder_rows(cfg: dict, W: dict, tok: np.ndarray, pos: np.ndarray, vis: np.ndarray,
-                 kv: list, L: int):
+                 kv: list, L: int, probe=None):
     """Run the base decoder over `rows` new tokens against a cache holding L committed rows.
 
     Row r sees cache rows 0..L-1 and new row m wherever vis[r, m].  K/V of new row r are
     written to cache row L + r.  Returns (h_last[rows, d], logits[rows, V]).
+
+    `probe(name, layer, value) -> value`, if given, is shown every named intermediate and
+    may replace it (diagnostics only: recording activations, or emulating a storage
+    precision); with probe=None the arithmetic is exactly as written.
     """
+    if probe is None:
+        probe = lambda name, layer, value: value
     d, nH, dh, F = cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ffn"]
     eps, theta = cfg["rms_eps"], cfg["rope_theta"]
     rows = len(tok)
@@ -125,11 +131,11 @@ def decoder_rows(cfg: dict, W: dict, tok: np.ndarray, pos: np.ndarray, vis: np.n
     layers = W["layers"]
     for l in range(cfg["n_layers"]):
         lw = layers[l]
-        m = rmsnorm(x, lw["attn_norm"], eps)
+        m = probe("attn_in", l, rmsnorm(x, lw["attn_norm"], eps))
         qkv = m @ _f(lw["wqkv"]).T
-        q = rope(qkv[:, :d].reshape(rows, nH, dh), pos, theta)
-        k = rope(qkv[:, d:2 * d].reshape(rows, nH, dh), pos, theta)
-        v = qkv[:, 2 * d:].reshape(rows, nH, dh)
+        q = probe("q", l, rope(qkv[:, :d].reshape(rows, nH, dh), pos, theta))
+        k = probe("k", l, rope(qkv[:, d:2 * d].reshape(rows, nH, dh), pos, theta))
+        v = probe("v", l, qkv[:, 2 * d:].reshape(rows, nH, dh))
         K, V = kv[l]
         K[:, L:L + rows, :] = np.transpose(k, (1, 0, 2))
         V[:, L:L + rows, :] = np.transpose(v, (1, 0, 2))
@@ -139,13 +145,15 @@ def decoder_rows(cfg: dict, W: dict, tok: np.ndarray, pos: np.ndarray, vis: np.n
             s = np.where(allowed, s, -np.inf)
             s = s - np.max(s, axis=1, keepdims=True)
             e = np.exp(s)
-            p = e / np.sum(e, axis=1, keepdims=True)
+            p = probe("p", l, e / np.sum(e, axis=1, keepdims=True))
             o[:, h, :] = p @ V[h, :L + rows, :]
+        o = probe("attn_out", l, o)
         x = x + o.reshape(rows, d) @ _f(lw["wo"]).T
-        m2 = rmsnorm(x, lw["ffn_norm"], eps)
+        m2 = probe("ffn_in", l, rmsnorm(x, lw["ffn_norm"], eps))
         gu = m2 @ _f(lw["w_gate_up"]).T
-        x = x + (silu(gu[:, :F]) * gu[:, F:]) @ _f(lw["w_down"]).T
-    h_last = rmsnorm(x, W["final_norm"], eps)
+        act = probe("ffn_act", l, silu(gu[:, :F]) * gu[:, F:])
+        x = probe("x", l, x + act @ _f(lw["w_down"]).T)
+    h_last = probe("h_last", -1, rmsnorm(x, W["final_norm"], eps))
     logits = h_last @ _f(W["lm_head"]).T
     return h_last, logits
 
@@ -264,7 +272,7 @@ def new_state(kv: list, L: int, root: int, cand: np.ndarray, flag: int) -> dict:
 
 def verify_step(cfg: dict, W: dict, parent: Sequence[int], rank: Sequence[int], st: dict,
                 force_ar: bool = False, forced_node_argmax: Optional[np.ndarray] = None,
-                forced_gate_hidden: Optional[np.ndarray] = None) -> dict:
+                forced_gate_hidden: Optional[np.ndarray] = None, probe=None) -> dict:
     """One decoding step for one sequence; updates `st` in place and returns everything
     the step computed.
 
@@ -282,7 +290,7 @@ def verify_step(cfg: dict, W: dict, parent: Sequence[int], rank: Sequence[int], 
     L = st["L"]
     tok = tree_tokens(st["root"], st["cand"], parent_s, rank_s)
     pos = L + depth
-    h_last, logits = decoder_rows(cfg, W, tok, pos, anc, st["kv"], L)
+    h_last, logits = decoder_rows(cfg, W, tok, pos, anc, st["kv"], L, probe)
     g = argmax_lowest(logits)
     if forced_node_argmax is not None:
         g = np.asarray(forced_node_argmax, dtype=np.int64)[:T]

@@ -24,7 +24,12 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
   const float scale = rsqrtf((float)dh);
   float qv[EPL], o[EPL];
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) { qv[e] = ld_f(q + lane + 64 * e) * scale; o[e] = 0.f; }
+  for (int e = 0; e < EPL; ++e) {
+    float qe = ld_f(q + lane + 64 * e);
+    if (a.q_lo_off) qe += ld_f(q + a.q_lo_off + lane + 64 * e);
+    qv[e] = qe * scale;
+    o[e] = 0.f;
+  }
   float m = -INFINITY, l = 0.f;
   for (int p = 0; p < L + Tb; ++p) {
     if (p >= L && !((mask >> (p - L)) & 1ull)) continue;
@@ -43,7 +48,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
   }
   T* out = reinterpret_cast<T*>(a.out) + (size_t)r * a.nH * dh + h * dh;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) st_f(out + lane + 64 * e, o[e] / l);
+  for (int e = 0; e < EPL; ++e) st_a(out + lane + 64 * e, a.out_lo_off, o[e] / l);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -95,9 +100,12 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   const int qnode = wave * 16 + lq;
   const bool qvalid = qnode < Tb;
   const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.q) + (size_t)(row0 + min(qnode, Tb - 1)) * (a.nH * DH) + h * DH;
-  uint4 qf[KS];
+  uint4 qf[KS], qfl[KS];   // hi and lo plane of q
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
+    qfl[ks] = *reinterpret_cast<const uint4*>(qrow + a.q_lo_off + ks * 32 + g * 8);
+  }
   const unsigned long long amask = qvalid ? a.anc[qnode] : 0ull;
   const float scale = rsqrtf((float)DH);
 
@@ -112,6 +120,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
       const int sw = (ks * 4 + g) ^ (key & (PPR - 1));
       const uint4 kf = *reinterpret_cast<const uint4*>(sK + key * ROWB + sw * 16);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[ks]),
+                                                    acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qfl[ks]),
                                                     acc, 0, 0, 0);
     }
 #pragma unroll
@@ -143,11 +153,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kp = 0; kp < CK / 32; ++kp) {
-    union { bf16_t u[8]; uint4 q; } pb;
+    union { bf16_t u[8]; uint4 q; } pb, pl;   // probabilities as hi + lo bf16, like every GEMM input
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       pb.u[e] = f32_to_bf16(s[2 * kp][e]);
+      pl.u[e] = f32_to_bf16(s[2 * kp][e] - bf16_to_f32(pb.u[e]));
       pb.u[4 + e] = f32_to_bf16(s[2 * kp + 1][e]);
+      pl.u[4 + e] = f32_to_bf16(s[2 * kp + 1][e] - bf16_to_f32(pb.u[4 + e]));
     }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
@@ -160,6 +172,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
         va.u[e] = *reinterpret_cast<const bf16_t*>(sV + key * ROWB + sw * 16 + (dh & 7) * 2);
       }
       o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va.q), __builtin_bit_cast(bf16x8_t, pb.q),
+                                                      o[dt], 0, 0, 0);
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va.q), __builtin_bit_cast(bf16x8_t, pl.q),
                                                       o[dt], 0, 0, 0);
     }
   }
@@ -194,7 +208,7 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
     den += w * a.part_ml[slot * 2 + 1];
     num += w * a.part_o[slot * DH + t];
   }
-  reinterpret_cast<bf16_t*>(a.out)[(size_t)r * a.nH * DH + h * DH + t] = f32_to_bf16(num / den);
+  st_a(reinterpret_cast<bf16_t*>(a.out) + (size_t)r * a.nH * DH + h * DH + t, a.out_lo_off, num / den);
 }
 
 hipError_t launch_attention(const AttnArgs& a, int dtype, int use_mfma, hipStream_t s) {

@@ -79,7 +79,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 512, max_split = 8;
+  int use_mfma_attn = 1, target_wgs = 512, max_split = 8, gemm_nsub = 2, act_split = 1;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
   void* workspace = nullptr;
@@ -134,6 +134,7 @@ void fill_dims(cerberus_ctx* c, const cerberus_config* cfg, const cerberus_tree*
   D.topk = cfg->topk; D.T = t->n_nodes; D.eps = cfg->rms_eps; D.threshold = cfg->entropy_threshold;
   c->elem = cfg->dtype == CERBERUS_F32 ? 4 : 2;
   c->R64 = (int)align_up((size_t)cfg->max_batch * t->n_nodes, 64);
+  D.R64 = c->R64;
   c->n_chunks_max = ceil_div(cfg->kv_capacity, 128);
 }
 
@@ -162,10 +163,11 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->g = b.take<int>(Rmax);
   c->x = b.take<float>((size_t)R64 * d);
   c->h_last = b.take<float>((size_t)R64 * d);
-  c->xn = b.take<unsigned char>((size_t)R64 * d * el);
-  c->q = b.take<unsigned char>((size_t)R64 * d * el);
-  c->attn = b.take<unsigned char>((size_t)R64 * d * el);
-  c->act = b.take<unsigned char>((size_t)R64 * D.Fpad * el);
+  const int planes = cfg.dtype == CERBERUS_BF16 ? 2 : 1;  // GEMM inputs: hi and lo plane in bf16 mode
+  c->xn = b.take<unsigned char>((size_t)planes * R64 * d * el);
+  c->q = b.take<unsigned char>((size_t)planes * R64 * d * el);
+  c->attn = b.take<unsigned char>((size_t)planes * R64 * d * el);
+  c->act = b.take<unsigned char>((size_t)planes * R64 * D.Fpad * el);
   const size_t nmax = (size_t)std::max(std::max(3 * d, 2 * D.F), D.V);
   c->part_floats = 8 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
   c->part = b.take<float>(c->part_floats);
@@ -173,7 +175,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->attn_po = b.take<float>(slots * D.dh);
   c->attn_ml = b.take<float>(slots * 2);
   for (int i = 0; i < 2; ++i) {
-    c->hsA[i] = b.take<unsigned char>((size_t)D.Hc * 16 * 2 * d * el);
+    c->hsA[i] = b.take<unsigned char>((size_t)planes * D.Hc * 16 * 2 * d * el);
     c->hsF[i] = b.take<float>((size_t)D.Hc * 16 * 2 * d);
   }
   c->final_norm = b.take<float>(d);
@@ -203,18 +205,20 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
 }
 
 // Split-K choice: enough workgroups to cover the chip a few times over, whole 256-wide k chunks.
-void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const* A, const int* lda, const void* const* W,
-               const int* N, const int* K, int out_rows, bool force_s1) {
+void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const* A, const int* lda, size_t lo_off,
+               const void* const* W, const int* N, const int* K, int out_rows, bool force_s1) {
   std::memset(&g, 0, sizeof g);
   g.n_prob = nprob;
-  const int cols = gemm_cols_per_wg(c->cfg.dtype);
+  g.nsub = c->gemm_nsub;
+  g.split = c->act_split;
+  const int cols = gemm_cols_per_wg(c->cfg.dtype, c->gemm_nsub);
   int total_tiles = 0;
   for (int p = 0; p < nprob; ++p) total_tiles += ceil_div(N[p], cols);
   float* out = c->part;
   int wg = 0;
   for (int p = 0; p < nprob; ++p) {
     GemmProb& P = g.p[p];
-    P.A = A[p]; P.W = W[p]; P.N = N[p]; P.lda = lda[p]; P.out_rows = out_rows;
+    P.A = A[p]; P.lo_off = lo_off; P.W = W[p]; P.N = N[p]; P.lda = lda[p]; P.out_rows = out_rows;
     if (c->cfg.dtype == CERBERUS_F32) {
       P.K = K[p]; P.S = 1; P.kps = 0;
     } else {
@@ -239,12 +243,12 @@ void build_plans(cerberus_ctx* c) {
   const int d = D.d, L = D.n_layers;
   c->p_qkv.resize(L); c->p_o.resize(L); c->p_gu.resize(L); c->p_down.resize(L);
   for (int l = 0; l < L; ++l) {
-    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, &c->wqkv[l], &N, &K, c->R64, false); }
-    { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, &c->wo[l], &N, &K, c->R64, false); }
-    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, &c->wgu[l], &N, &K, c->R64, false); }
-    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, &c->wdown[l], &N, &K, c->R64, false); }
+    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, c->R64, false); }
+    { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wo[l], &N, &K, c->R64, false); }
+    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, c->R64, false); }
+    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, c->R64, false); }
   }
-  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, &c->lm_head, &N, &K, c->R64, false); }
+  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, c->R64, false); }
   c->p_res.resize(D.R);
   const void* A[CERBERUS_MAX_HEADS]; const void* W[CERBERUS_MAX_HEADS];
   int lda[CERBERUS_MAX_HEADS], N[CERBERUS_MAX_HEADS], K[CERBERUS_MAX_HEADS];
@@ -255,7 +259,7 @@ void build_plans(cerberus_ctx* c) {
       lda[i] = 2 * d;
       N[i] = K[i] = head_width(c->cfg, i, s);
     }
-    plan_gemm(c, c->p_res[s], D.Hc, A, lda, W, N, K, 16, false);
+    plan_gemm(c, c->p_res[s], D.Hc, A, lda, (size_t)D.Hc * 16 * 2 * d, W, N, K, 16, false);
   }
   for (int i = 0; i < D.Hc; ++i) {
     A[i] = (const unsigned char*)c->hsA[D.R & 1] + (size_t)i * 16 * 2 * d * c->elem;
@@ -264,7 +268,7 @@ void build_plans(cerberus_ctx* c) {
     N[i] = D.V;
     K[i] = head_width(c->cfg, i, D.R - 1);
   }
-  plan_gemm(c, c->p_fc, D.Hc, A, lda, W, N, K, 16, true);
+  plan_gemm(c, c->p_fc, D.Hc, A, lda, (size_t)D.Hc * 16 * 2 * d, W, N, K, 16, true);
 }
 
 int check_state(const cerberus_ctx* c, const cerberus_state* st, int batch) {
@@ -314,7 +318,7 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
     void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
     HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, rows_max, s));
     AttnArgs aa{};
-    aa.q = c->q; aa.kv = kv_layer; aa.out = c->attn; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
+    aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
     aa.anc = c->tree.anc; aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
     aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
@@ -524,7 +528,7 @@ int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* str
   double total = 0.0;
   auto run = [&](const GemmBatch& g) -> int {
     for (int p = 0; p < g.n_prob; ++p)
-      total += ((double)g.p[p].N * g.p[p].K + (double)rows * g.p[p].K) * ctx->elem;
+      total += ((double)g.p[p].N * g.p[p].K + (double)rows * g.p[p].K * (g.split && ctx->elem == 2 ? 2 : 1)) * ctx->elem;
     return run_gemm(ctx, g, nullptr, rows, rows, nullptr, 0, s);
   };
   if (kind <= 3) {
@@ -557,6 +561,14 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
   } else if (n == "gemm_target_wgs") {
     if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "gemm_target_wgs out of 1..65536");
     ctx->target_wgs = value;
+    build_plans(ctx);
+  } else if (n == "gemm_nsub") {
+    if (value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub must be 2 or 4");
+    ctx->gemm_nsub = value;
+    build_plans(ctx);
+  } else if (n == "act_split") {
+    if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "act_split must be 0 or 1");
+    ctx->act_split = value;
     build_plans(ctx);
   } else if (n == "gemm_max_split") {
     if (value < 1 || value > 8) return fail(CERBERUS_ERR_ARG, "gemm_max_split out of 1..8");

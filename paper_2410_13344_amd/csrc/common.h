@@ -27,7 +27,18 @@ template <typename T> __device__ __forceinline__ void st_f(T* p, float v);
 template <> __device__ __forceinline__ void st_f<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void st_f<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// Store of a GEMM input.  In bf16 mode an activation v is kept as two bf16 planes `lo_off` elements
+// apart, hi = bf16(v) and lo = bf16(v - hi): the GEMM multiplies both by the same weight fragment, so
+// activations carry about 16 significant bits at no extra HBM traffic (the MFMA units idle most of
+// the time in this weight-streaming regime).  bf16-rounded GEMM inputs alone put ~4e-2 rms error on
+// the logits of a 32-layer random-init model.
+template <typename T> __device__ __forceinline__ void st_a(T* p, size_t lo_off, float v);
+template <> __device__ __forceinline__ void st_a<float>(float* p, size_t, float v) { *p = v; }
+template <> __device__ __forceinline__ void st_a<bf16_t>(bf16_t* p, size_t lo_off, float v) {
+  const bf16_t hi = f32_to_bf16(v);
+  *p = hi;
+  p[lo_off] = f32_to_bf16(v - bf16_to_f32(hi));
+}
 
 // ---------------------------------------------------------------------------------------------
 // per-step row map: packed rows of all sequences (sequence b owns rows seq_row0[b] .. +seq_T[b])
@@ -55,7 +66,8 @@ struct TreeDev {
 // GEMM launch description: out[split][row][n] = sum_k A[row][k] * W[n][k] over the split's k range
 // ---------------------------------------------------------------------------------------------
 struct GemmProb {
-  const void* A;  // [rows_alloc][lda], element type of the mode
+  const void* A;  // [rows_alloc][lda], element type of the mode; bf16: the lo plane follows lo_off elements later
+  size_t lo_off;
   const void* W;  // bf16 mode: MFMA-tile packed; f32 mode: row-major [N][K]
   float* out;     // [S][out_rows][N]
   int N, K;       // bf16 mode: K is the padded K (multiple of 32)
@@ -75,17 +87,21 @@ struct GemmBatch {
   int rows_static;
   const int* skip_flags;         // if non-null and all n_skip flags are non-zero: nothing to do
   int n_skip;
+  int nsub;                      // bf16: 16-column slabs per wave (2 or 4); a workgroup covers 64*nsub columns
+  int split;                     // bf16: 1 = multiply the hi and the lo activation plane, 0 = hi only
 };
 
 // launchers (defined next to their kernels)
 hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t s);
 hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int Kpad, hipStream_t s);
-int gemm_cols_per_wg(int dtype);
+int gemm_cols_per_wg(int dtype, int nsub);
 
 struct AttnArgs {
-  const void* q;     // [rows][nH*dh]
+  const void* q;     // [rows][nH*dh]; bf16: lo plane q_lo_off elements later (0 in fp32 mode)
+  size_t q_lo_off;
   const void* kv;    // layer base: [2][Bmax][nH][cap][dh]
-  void* out;         // [rows][nH*dh] attention output (GEMM A operand)
+  void* out;         // [rows][nH*dh] attention output (GEMM A operand; bf16: lo plane out_lo_off elements later)
+  size_t out_lo_off;
   float* part_o;     // [B][nH][n_chunks_max][64][dh]
   float* part_ml;    // [B][nH][n_chunks_max][64][2]
   RowMap rm;

@@ -40,12 +40,13 @@ hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int K
 
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA GEMM.  Workgroup = 4 waves; wave w owns NSUB adjacent 16-column slabs; a workgroup
-// covers 64*NSUB columns, MT*16 rows and one split of K (whole chunks of 256 k).  A is staged
-// through a double-buffered LDS tile per chunk (512 B rows, 16-byte pieces XOR-swizzled by the row
-// index so the 16 lanes of an MFMA row group hit 64 distinct banks); the main loop has no
-// branches, so the weight loads stay in flight across chunk boundaries.
+// covers 64*NSUB columns, MT*16 rows and one split of K.  A is staged through a double-buffered LDS
+// tile of 512-byte rows: 8 k-steps of one plane, or with SPLIT 4 k-steps of the hi plane followed by
+// the same 4 k-steps of the lo plane.  16-byte pieces are XOR-swizzled by the row index so the 16
+// lanes of an MFMA row group hit 64 distinct banks.  The main loop has no branches, so the weight
+// loads stay in flight across chunk boundaries.
 // ---------------------------------------------------------------------------------------------
-constexpr int kLdsRow = 512;   // 256 bf16, pieces swizzled
+constexpr int kLdsRow = 512;
 constexpr int kRing = 4;       // k-steps of weights in flight per wave
 
 __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
@@ -55,7 +56,7 @@ __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
   return all;
 }
 
-template <int MT, int NSUB>
+template <int MT, int NSUB, int SPLIT>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   if (gemm_skip(g)) return;
   const int rows = g.n_rows ? *g.n_rows : g.rows_static;
@@ -68,10 +69,11 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   const int local = (int)blockIdx.x - g.tile0[pi];
   const int split = local % P.S;
   const int ntile = local / P.S;
-  const int ksteps = P.K / 32;               // K is a multiple of 256: whole chunks only
+  constexpr int KSC = SPLIT ? 4 : 8;         // k-steps per LDS chunk
+  const int ksteps = P.K / 32;               // K is a multiple of 256
   const int ks0 = split * P.kps;             // kps is a multiple of 8
   const int ks1 = min(ks0 + P.kps, ksteps);
-  const int nchunks = (ks1 - ks0) / 8;
+  const int nchunks = (ks1 - ks0) / KSC;
   if (nchunks <= 0) return;                  // uniform over the workgroup
 
   const int wave = threadIdx.x >> 6;
@@ -105,7 +107,10 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
     for (int i = 0; i < kApt; ++i) {
       const int idx = threadIdx.x + i * 256;
       const int r = idx >> 5, pc = idx & 31;
-      areg[i] = *reinterpret_cast<const uint4*>(A + (size_t)(m0 + r) * P.lda + (size_t)(ks0 + chunk * 8) * 32 + pc * 8);
+      const bf16_t* src = A + (size_t)(m0 + r) * P.lda + (size_t)(ks0 + chunk * KSC) * 32;
+      if (SPLIT) src += (size_t)(pc >> 4) * P.lo_off + (pc & 15) * 8;
+      else src += pc * 8;
+      areg[i] = *reinterpret_cast<const uint4*>(src);
     }
   };
   auto store_a = [&](int buf) {
@@ -130,9 +135,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   for (int c = 0; c < nchunks; ++c) {
     load_a(min(c + 1, nchunks - 1));
     const unsigned char* L = lds + (c & 1) * kBuf + a_row * kLdsRow;
-    const int kb = ks0 + c * 8;
+    const int kb = ks0 + c * KSC;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < KSC; ++s) {
       uint4 b[NSUB];
 #pragma unroll
       for (int j = 0; j < NSUB; ++j) {
@@ -146,6 +151,13 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
         for (int j = 0; j < NSUB; ++j)
           acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                                __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);
+        if (SPLIT) {
+          const uint4 al = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((16 + s * 4 + a_grp) ^ a_row) * 16));
+#pragma unroll
+          for (int j = 0; j < NSUB; ++j)
+            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, al),
+                                                                 __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);
+        }
       }
     }
     store_a((c + 1) & 1);
@@ -193,7 +205,18 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const GemmBatch g) {
   }
 }
 
-int gemm_cols_per_wg(int dtype) { return dtype == 0 ? 64 : 128; }
+int gemm_cols_per_wg(int dtype, int nsub) { return dtype == 0 ? 64 : 64 * nsub; }
+
+template <int MT>
+static void launch_bf16(const GemmBatch& g, dim3 grid, hipStream_t s) {
+  if (g.nsub == 4) {
+    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 1>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 0>), grid, dim3(256), 0, s, g);
+  } else {
+    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 2, 1>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<MT, 2, 0>), grid, dim3(256), 0, s, g);
+  }
+}
 
 hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t s) {
   const int wgs = g.tile0[g.n_prob];
@@ -201,11 +224,11 @@ hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t 
   if (dtype == 0) {
     hipLaunchKernelGGL(k_gemm_f32, dim3(wgs, (rows_max + 15) / 16), dim3(256), 0, s, g);
   } else if (rows_max <= 16) {
-    hipLaunchKernelGGL((k_gemm_bf16<1, 2>), dim3(wgs, 1), dim3(256), 0, s, g);
+    launch_bf16<1>(g, dim3(wgs, 1), s);
   } else if (rows_max <= 32) {
-    hipLaunchKernelGGL((k_gemm_bf16<2, 2>), dim3(wgs, 1), dim3(256), 0, s, g);
+    launch_bf16<2>(g, dim3(wgs, 1), s);
   } else {
-    hipLaunchKernelGGL((k_gemm_bf16<4, 2>), dim3(wgs, (rows_max + 63) / 64), dim3(256), 0, s, g);
+    launch_bf16<4>(g, dim3(wgs, (rows_max + 63) / 64), s);
   }
   return hipGetLastError();
 }

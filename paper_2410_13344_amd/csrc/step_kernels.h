@@ -7,6 +7,7 @@ namespace cerb {
 
 struct Dims {
   int n_layers, d, nH, dh, F, Fpad, V, Hc, R, sb, dtype, Bmax, cap, topk, T;
+  int R64;  // rows allocated per activation plane
   float eps, threshold;
 };
 

@@ -127,7 +127,7 @@ hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, floa
 template <typename T>
 __global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ part, int S,
                                                      size_t pstride, const float* __restrict__ gain, float eps,
-                                                     T* __restrict__ out, float* __restrict__ out_f32,
+                                                     T* __restrict__ out, size_t lo_off, float* __restrict__ out_f32,
                                                      float* __restrict__ tap, const RowMap rm, int d, int T_tree) {
   __shared__ float sh[4];
   const int r = blockIdx.x;
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, cons
   float* tp = tap ? tap + ((size_t)rm.row_seq[r] * T_tree + rm.row_node[r]) * d : nullptr;
   for (int c = threadIdx.x; c < d; c += 256) {
     const float v = xr[c] * gain[c] * sc;
-    st_f(out + (size_t)r * d + c, v);
+    st_a(out + (size_t)r * d + c, lo_off, v);
     if (out_f32) out_f32[(size_t)r * d + c] = v;
     if (tp) tp[c] = v;
   }
@@ -155,10 +155,10 @@ hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const f
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s) {
   if (D.dtype == 0)
     hipLaunchKernelGGL((k_add_rmsnorm<float>), dim3(rows_max), dim3(256), 0, s, x, part, S, pstride, gain, D.eps, (float*)out,
-                       out_f32, tap, rm, D.d, D.T);
+                       (size_t)0, out_f32, tap, rm, D.d, D.T);
   else
     hipLaunchKernelGGL((k_add_rmsnorm<bf16_t>), dim3(rows_max), dim3(256), 0, s, x, part, S, pstride, gain, D.eps,
-                       (bf16_t*)out, out_f32, tap, rm, D.d, D.T);
+                       (bf16_t*)out, (size_t)D.R64 * D.d, out_f32, tap, rm, D.d, D.T);
   return hipGetLastError();
 }
 
@@ -168,7 +168,7 @@ hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const f
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const float* __restrict__ inv_freq,
-                          const RowMap rm, T* __restrict__ q, T* __restrict__ kv_layer, const Dims D) {
+                          const RowMap rm, T* __restrict__ q, size_t q_lo_off, T* __restrict__ kv_layer, const Dims D) {
   const int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
   if (r >= *rm.n_rows) return;
   const int b = rm.row_seq[r], node = rm.row_node[r];
@@ -181,8 +181,8 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
   }
   float sn, cs;
   sincosf((float)rm.row_pos[r] * inv_freq[j], &sn, &cs);
-  st_f(q + (size_t)r * d + c0, v[0] * cs - v[1] * sn);
-  st_f(q + (size_t)r * d + c1, v[0] * sn + v[1] * cs);
+  st_a(q + (size_t)r * d + c0, q_lo_off, v[0] * cs - v[1] * sn);
+  st_a(q + (size_t)r * d + c1, q_lo_off, v[0] * sn + v[1] * cs);
   const size_t row = (size_t)(rm.seq_L[b] + node);
   T* Kr = kv_layer + (((size_t)(0 * D.Bmax + b) * D.nH + h) * D.cap + row) * dh;
   T* Vr = kv_layer + (((size_t)(1 * D.Bmax + b) * D.nH + h) * D.cap + row) * dh;
@@ -196,17 +196,17 @@ hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, in
                           const float* inv_freq, void* q, void* kv_layer, int rows_max, hipStream_t s) {
   dim3 grid(rows_max, D.nH), block(D.dh / 2);
   if (D.dtype == 0)
-    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (float*)kv_layer, D);
+    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (size_t)0, (float*)kv_layer, D);
   else
     hipLaunchKernelGGL((k_rope_kv<bf16_t>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (bf16_t*)q,
-                       (bf16_t*)kv_layer, D);
+                       (size_t)D.R64 * D.d, (bf16_t*)kv_layer, D);
   return hipGetLastError();
 }
 
 // act = SiLU(gate) * up from the gate/up partials ([.., 2F]: gate columns first)
 template <typename T>
 __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, int S, size_t pstride, T* __restrict__ act,
-                                                const RowMap rm, int F, int Fpad) {
+                                                size_t lo_off, const RowMap rm, int F, int Fpad) {
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   const int f = blockIdx.y * 256 + threadIdx.x;
@@ -217,14 +217,14 @@ __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, 
     g += p[f];
     u += p[F + f];
   }
-  st_f(act + (size_t)r * Fpad + f, g / (1.0f + expf(-g)) * u);
+  st_a(act + (size_t)r * Fpad + f, lo_off, g / (1.0f + expf(-g)) * u);
 }
 
 hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
                          int rows_max, hipStream_t s) {
   dim3 grid(rows_max, (D.F + 255) / 256);
-  if (D.dtype == 0) hipLaunchKernelGGL((k_swiglu<float>), grid, dim3(256), 0, s, part, S, pstride, (float*)act, rm, D.F, D.Fpad);
-  else hipLaunchKernelGGL((k_swiglu<bf16_t>), grid, dim3(256), 0, s, part, S, pstride, (bf16_t*)act, rm, D.F, D.Fpad);
+  if (D.dtype == 0) hipLaunchKernelGGL((k_swiglu<float>), grid, dim3(256), 0, s, part, S, pstride, (float*)act, (size_t)0, rm, D.F, D.Fpad);
+  else hipLaunchKernelGGL((k_swiglu<bf16_t>), grid, dim3(256), 0, s, part, S, pstride, (bf16_t*)act, (size_t)D.R64 * D.Fpad, rm, D.F, D.Fpad);
   return hipGetLastError();
 }
 
@@ -386,7 +386,7 @@ hipError_t launch_gate(int d, float threshold, const float* base, const int* row
 template <typename T>
 __global__ __launch_bounds__(256) void k_heads_prepare(const Dims D, const float* __restrict__ h_last,
                                                        const int* __restrict__ last_row, float* __restrict__ hsF,
-                                                       T* __restrict__ hsA) {
+                                                       T* __restrict__ hsA, size_t lo_off) {
   const int b = blockIdx.x;
   const int lr = last_row[b];
   const int d = D.d, ld = 2 * d;
@@ -395,24 +395,24 @@ __global__ __launch_bounds__(256) void k_heads_prepare(const Dims D, const float
     for (int i = 0; i < D.Hc; ++i) {
       const size_t o = ((size_t)i * 16 + b) * ld + c;
       hsF[o] = v;
-      st_f(hsA + o, v);
-      if (D.sb == 0 && i >= 1) { hsF[o + d] = v; st_f(hsA + o + d, v); }
+      st_a(hsA + o, lo_off, v);
+      if (D.sb == 0 && i >= 1) { hsF[o + d] = v; st_a(hsA + o + d, lo_off, v); }
     }
   }
 }
 
 hipError_t launch_heads_prepare(const Dims& D, const float* h_last, const int* last_row, float* hsF, void* hsA, int batch,
                                 hipStream_t s) {
-  if (D.dtype == 0) hipLaunchKernelGGL((k_heads_prepare<float>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (float*)hsA);
-  else hipLaunchKernelGGL((k_heads_prepare<bf16_t>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (bf16_t*)hsA);
+  if (D.dtype == 0) hipLaunchKernelGGL((k_heads_prepare<float>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (float*)hsA, (size_t)0);
+  else hipLaunchKernelGGL((k_heads_prepare<bf16_t>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (bf16_t*)hsA, (size_t)D.Hc * 16 * 2 * D.d);
   return hipGetLastError();
 }
 
 // Resblock tail: Output = SiLU((W h + b) + h) from the GEMM partials of W h (Section 4.1).
 template <typename T>
 __global__ __launch_bounds__(256) void k_resblock_finish(const ResFinishArgs a, const float* __restrict__ curF,
-                                                         float* __restrict__ nxtF, T* __restrict__ nxtA, int d, int Hc,
-                                                         int link_next) {
+                                                         float* __restrict__ nxtF, T* __restrict__ nxtA, size_t lo_off, int d,
+                                                         int Hc, int link_next) {
   const int i = blockIdx.x, b = blockIdx.y;
   const int col = blockIdx.z * 256 + threadIdx.x;
   const int w = a.width[i], ld = 2 * d;
@@ -422,11 +422,11 @@ __global__ __launch_bounds__(256) void k_resblock_finish(const ResFinishArgs a, 
   for (int s = 0; s < a.S[i]; ++s) v += a.part[i][s * a.pstride[i] + (size_t)b * w + col];
   v = v / (1.0f + expf(-v));
   nxtF[o] = v;
-  st_f(nxtA + o, v);
+  st_a(nxtA + o, lo_off, v);
   if (link_next && i + 1 < Hc && col < d) {
     const size_t o2 = ((size_t)(i + 1) * 16 + b) * ld + d + col;
     nxtF[o2] = v;
-    st_f(nxtA + o2, v);
+    st_a(nxtA + o2, lo_off, v);
   }
 }
 
@@ -434,9 +434,9 @@ hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const f
                                   int link_next, int batch, hipStream_t s) {
   dim3 grid(D.Hc, batch, (2 * D.d + 255) / 256);
   if (D.dtype == 0)
-    hipLaunchKernelGGL((k_resblock_finish<float>), grid, dim3(256), 0, s, a, curF, nxtF, (float*)nxtA, D.d, D.Hc, link_next);
+    hipLaunchKernelGGL((k_resblock_finish<float>), grid, dim3(256), 0, s, a, curF, nxtF, (float*)nxtA, (size_t)0, D.d, D.Hc, link_next);
   else
-    hipLaunchKernelGGL((k_resblock_finish<bf16_t>), grid, dim3(256), 0, s, a, curF, nxtF, (bf16_t*)nxtA, D.d, D.Hc, link_next);
+    hipLaunchKernelGGL((k_resblock_finish<bf16_t>), grid, dim3(256), 0, s, a, curF, nxtF, (bf16_t*)nxtA, (size_t)D.Hc * 16 * 2 * D.d, D.d, D.Hc, link_next);
   return hipGetLastError();
 }
 
