@@ -102,6 +102,7 @@ int validate(const cerberus_config* c, const cerberus_tree* t) {
   if (c->head_dim != 64 && c->head_dim != 128) return fail(CERBERUS_ERR_SHAPE, "head_dim must be 64 or 128");
   if (c->d_model != c->n_heads * c->head_dim) return fail(CERBERUS_ERR_SHAPE, "d_model != n_heads * head_dim");
   if (c->d_ffn % 8 || c->vocab % 16) return fail(CERBERUS_ERR_SHAPE, "d_ffn must be a multiple of 8 and vocab of 16");
+  if (c->d_model > 8192 || c->vocab > 65536) return fail(CERBERUS_ERR_SHAPE, "d_model above 8192 or vocab above 65536");
   if (c->dtype == CERBERUS_BF16 && c->d_model % 256) return fail(CERBERUS_ERR_SHAPE, "bf16 mode needs d_model to be a multiple of 256");
   if (c->n_cerb_heads < 1 || c->n_cerb_heads > CERBERUS_MAX_HEADS) return fail(CERBERUS_ERR_SHAPE, "n_cerb_heads out of 1..%d", CERBERUS_MAX_HEADS);
   if (c->n_resblocks < 1 || c->n_resblocks > 16) return fail(CERBERUS_ERR_SHAPE, "n_resblocks out of 1..16");

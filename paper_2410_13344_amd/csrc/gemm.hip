@@ -98,42 +98,39 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
 #pragma unroll
     for (int j = 0; j < NSUB; ++j) acc[mt][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  // activation chunk c+1 travels global -> registers while chunk c is consumed from LDS
+  // activation chunk c+1 travels global -> registers while chunk c is consumed from LDS.
+  // (Plain unrolled loops with constant indices on purpose: staging arrays touched through a
+  // lambda end up in scratch memory, and a scratch round trip inside the loop serialises the whole
+  // in-order load queue.)
   constexpr int kApt = MT * 2;  // 16-byte pieces per thread per chunk
   const bf16_t* A = reinterpret_cast<const bf16_t*>(P.A);
+  const bf16_t* a_src[kApt];
+  int a_dst[kApt];
+#pragma unroll
+  for (int i = 0; i < kApt; ++i) {
+    const int idx = threadIdx.x + i * 256;
+    const int r = idx >> 5, pc = idx & 31;
+    a_src[i] = A + (size_t)(m0 + r) * P.lda + (size_t)ks0 * 32 +
+               (SPLIT ? (size_t)(pc >> 4) * P.lo_off + (pc & 15) * 8 : (size_t)pc * 8);
+    a_dst[i] = r * kLdsRow + ((pc ^ (r & 15)) * 16);
+  }
   uint4 areg[kApt];
-  auto load_a = [&](int chunk) {
 #pragma unroll
-    for (int i = 0; i < kApt; ++i) {
-      const int idx = threadIdx.x + i * 256;
-      const int r = idx >> 5, pc = idx & 31;
-      const bf16_t* src = A + (size_t)(m0 + r) * P.lda + (size_t)(ks0 + chunk * KSC) * 32;
-      if (SPLIT) src += (size_t)(pc >> 4) * P.lo_off + (pc & 15) * 8;
-      else src += pc * 8;
-      areg[i] = *reinterpret_cast<const uint4*>(src);
-    }
-  };
-  auto store_a = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < kApt; ++i) {
-      const int idx = threadIdx.x + i * 256;
-      const int r = idx >> 5, pc = idx & 31;
-      *reinterpret_cast<uint4*>(lds + buf * kBuf + r * kLdsRow + ((pc ^ (r & 15)) * 16)) = areg[i];
-    }
-  };
-
-  load_a(0);
+  for (int i = 0; i < kApt; ++i) areg[i] = *reinterpret_cast<const uint4*>(a_src[i]);
   uint4 ring[kRing][NSUB];
 #pragma unroll
   for (int i = 0; i < kRing; ++i)
 #pragma unroll
     for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + i, ks1 - 1) * 64];
-  store_a(0);
+#pragma unroll
+  for (int i = 0; i < kApt; ++i) *reinterpret_cast<uint4*>(lds + a_dst[i]) = areg[i];
   __syncthreads();
 
   const int a_row = lane & 15, a_grp = lane >> 4;  // (mt*16 + a_row) & 15 == a_row
   for (int c = 0; c < nchunks; ++c) {
-    load_a(min(c + 1, nchunks - 1));
+    const int cn = min(c + 1, nchunks - 1);
+#pragma unroll
+    for (int i = 0; i < kApt; ++i) areg[i] = *reinterpret_cast<const uint4*>(a_src[i] + (size_t)cn * (KSC * 32));
     const unsigned char* L = lds + (c & 1) * kBuf + a_row * kLdsRow;
     const int kb = ks0 + c * KSC;
 #pragma unroll
@@ -160,7 +157,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
         }
       }
     }
-    store_a((c + 1) & 1);
+    unsigned char* Ln = lds + ((c + 1) & 1) * kBuf;
+#pragma unroll
+    for (int i = 0; i < kApt; ++i) *reinterpret_cast<uint4*>(Ln + a_dst[i]) = areg[i];
     __syncthreads();
   }
 

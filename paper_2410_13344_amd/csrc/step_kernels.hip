@@ -122,42 +122,60 @@ hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, floa
 
 // ---------------------------------------------------------------------------------------------
 // x += sum of the previous GEMM's split-K partials (the residual add), then RMSNorm:
-// out = x * gain / sqrt(mean(x^2) + eps), rounded to the GEMM input type.
-// ---------------------------------------------------------------------------------------------
+// out = x * gain / sqrt(mean(x^2) + eps), rounded to the GEMM input type.  d <= 8192, d % 4 == 0.
+// One workgroup of 512 threads per row; a thread owns up to four float4 column groups, loaded once
+// (x and every partial, all loads independent), so the row is read exactly once.
 template <typename T>
-__global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ part, int S,
+__global__ __launch_bounds__(512) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ part, int S,
                                                      size_t pstride, const float* __restrict__ gain, float eps,
                                                      T* __restrict__ out, size_t lo_off, float* __restrict__ out_f32,
                                                      float* __restrict__ tap, const RowMap rm, int d, int T_tree) {
-  __shared__ float sh[4];
+  __shared__ float sh[8];
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   float* xr = x + (size_t)r * d;
+  float4 v[4];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += 256) {
-    float v = xr[c];
-    for (int s = 0; s < S; ++s) v += part[s * pstride + (size_t)r * d + c];
-    if (S > 0) xr[c] = v;
-    ss += v * v;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int c = (it * 512 + threadIdx.x) * 4;
+    v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c < d) {
+      v[it] = *reinterpret_cast<const float4*>(xr + c);
+      for (int s = 0; s < S; ++s) {
+        const float4 p = *reinterpret_cast<const float4*>(part + s * pstride + (size_t)r * d + c);
+        v[it].x += p.x; v[it].y += p.y; v[it].z += p.z; v[it].w += p.w;
+      }
+      if (S > 0) *reinterpret_cast<float4*>(xr + c) = v[it];
+      ss += v[it].x * v[it].x + v[it].y * v[it].y + v[it].z * v[it].z + v[it].w * v[it].w;
+    }
   }
   ss = block_sum(ss, sh);
   const float sc = 1.0f / sqrtf(ss / (float)d + eps);
   float* tp = tap ? tap + ((size_t)rm.row_seq[r] * T_tree + rm.row_node[r]) * d : nullptr;
-  for (int c = threadIdx.x; c < d; c += 256) {
-    const float v = xr[c] * gain[c] * sc;
-    st_a(out + (size_t)r * d + c, lo_off, v);
-    if (out_f32) out_f32[(size_t)r * d + c] = v;
-    if (tp) tp[c] = v;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int c = (it * 512 + threadIdx.x) * 4;
+    if (c < d) {
+      const float4 g = *reinterpret_cast<const float4*>(gain + c);
+      const float o[4] = {v[it].x * g.x * sc, v[it].y * g.y * sc, v[it].z * g.z * sc, v[it].w * g.w * sc};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        st_a(out + (size_t)r * d + c + e, lo_off, o[e]);
+        if (out_f32) out_f32[(size_t)r * d + c + e] = o[e];
+        if (tp) tp[c + e] = o[e];
+      }
+    }
   }
 }
 
 hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s) {
   if (D.dtype == 0)
-    hipLaunchKernelGGL((k_add_rmsnorm<float>), dim3(rows_max), dim3(256), 0, s, x, part, S, pstride, gain, D.eps, (float*)out,
+    hipLaunchKernelGGL((k_add_rmsnorm<float>), dim3(rows_max), dim3(512), 0, s, x, part, S, pstride, gain, D.eps, (float*)out,
                        (size_t)0, out_f32, tap, rm, D.d, D.T);
   else
-    hipLaunchKernelGGL((k_add_rmsnorm<bf16_t>), dim3(rows_max), dim3(256), 0, s, x, part, S, pstride, gain, D.eps,
+    hipLaunchKernelGGL((k_add_rmsnorm<bf16_t>), dim3(rows_max), dim3(512), 0, s, x, part, S, pstride, gain, D.eps,
                        (bf16_t*)out, (size_t)D.R64 * D.d, out_f32, tap, rm, D.d, D.T);
   return hipGetLastError();
 }
@@ -232,20 +250,23 @@ hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int
 // g[row] = argmax over the vocabulary of the LM-head logits (Algorithm 1 line 9 at every node),
 // lowest id on ties.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_row_argmax(const float* __restrict__ part, int S, size_t pstride, int* __restrict__ g,
-                                                    const cerberus_taps tp, const RowMap rm, int V, int T_tree) {
-  __shared__ float shv[4];
-  __shared__ int shi[4];
+__global__ __launch_bounds__(1024) void k_row_argmax(const float* __restrict__ part, int S, size_t pstride, int* __restrict__ g,
+                                                     const cerberus_taps tp, const RowMap rm, int V, int T_tree) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   const size_t slot = (size_t)rm.row_seq[r] * T_tree + rm.row_node[r];
   float bv = -INFINITY;
   int bi = INT_MAX;
-  for (int v = threadIdx.x; v < V; v += 256) {
-    float val = 0.f;
-    for (int s = 0; s < S; ++s) val += part[s * pstride + (size_t)r * V + v];
-    if (tp.logits) tp.logits[slot * V + v] = val;
-    better(bv, bi, val, v);
+  for (int v = threadIdx.x * 4; v < V; v += 4096) {   // V % 16 == 0
+    float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < S; ++s) {
+      const float4 p = *reinterpret_cast<const float4*>(part + s * pstride + (size_t)r * V + v);
+      val.x += p.x; val.y += p.y; val.z += p.z; val.w += p.w;
+    }
+    if (tp.logits) *reinterpret_cast<float4*>(tp.logits + slot * V + v) = val;
+    better(bv, bi, val.x, v); better(bv, bi, val.y, v + 1); better(bv, bi, val.z, v + 2); better(bv, bi, val.w, v + 3);
   }
   block_argmax(bv, bi, shv, shi);
   if (threadIdx.x == 0) {
@@ -258,7 +279,7 @@ __global__ __launch_bounds__(256) void k_row_argmax(const float* __restrict__ pa
 
 hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, int* g,
                              const cerberus_taps& tp, int rows_max, hipStream_t s) {
-  hipLaunchKernelGGL(k_row_argmax, dim3(rows_max), dim3(256), 0, s, part, S, pstride, g, tp, rm, D.V, D.T);
+  hipLaunchKernelGGL(k_row_argmax, dim3(rows_max), dim3(1024), 0, s, part, S, pstride, g, tp, rm, D.V, D.T);
   return hipGetLastError();
 }
 
@@ -305,34 +326,33 @@ hipError_t launch_accept(const Dims& D, const TreeDev& tr, const RowMap& rm, con
 
 // ---------------------------------------------------------------------------------------------
 // KV compaction: cache row L + path[j] -> row L + j for j = 1..a-1, in every layer, K and V, head.
-// A thread owns one 16-byte column piece of a (layer, K|V, head) slice: it loads the pieces of all
-// source rows (j ascending) and only then stores them.  Row L + j can only be the source of a copy
-// j' <= j, whose load was issued no later than load j, and loads return in order, so every store
-// follows all loads of the row it overwrites; different threads touch disjoint bytes.
+// A workgroup owns one (layer, K|V, head) slice; thread (t, j) moves the t-th 16-byte piece of source
+// row j.  A source row of one copy can be the destination of another (path[1] = 3 and j = 3), so
+// every thread first loads its piece into a register, the whole workgroup waits for those loads and
+// meets at a barrier, and only then are the pieces stored: no store can overtake a load.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_compact(const Dims D, const RowMap rm, const cerberus_state st,
-                                                const int* __restrict__ path, int elem_bytes) {
+__global__ __launch_bounds__(512) void k_compact(const Dims D, const RowMap rm, const cerberus_state st,
+                                                 const int* __restrict__ path, int elem_bytes) {
   const int lk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int a = st.accept_len[b];
-  if (a <= 1) return;
+  if (a <= 1) return;                       // uniform over the workgroup
   const int pieces = D.dh * elem_bytes / 16;
-  const int t = threadIdx.x;
-  if (t >= pieces) return;
+  const int t = threadIdx.x, j = threadIdx.y + 1;
+  const bool active = t < pieces && j < a;
   const int L = rm.seq_L[b], W = D.Hc + 1;
   const size_t row_bytes = (size_t)D.dh * elem_bytes;
   unsigned char* base = reinterpret_cast<unsigned char*>(st.kv) + (((size_t)lk * D.Bmax + b) * D.nH + h) * D.cap * row_bytes;
-  uint4 regs[CERBERUS_MAX_HEADS];
-#pragma unroll
-  for (int j = 1; j <= CERBERUS_MAX_HEADS; ++j)
-    if (j < a) regs[j - 1] = reinterpret_cast<const uint4*>(base + (size_t)(L + path[b * W + j]) * row_bytes)[t];
-#pragma unroll
-  for (int j = 1; j <= CERBERUS_MAX_HEADS; ++j)
-    if (j < a) reinterpret_cast<uint4*>(base + (size_t)(L + j) * row_bytes)[t] = regs[j - 1];
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (active) v = reinterpret_cast<const uint4*>(base + (size_t)(L + path[b * W + j]) * row_bytes)[t];
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the row is in registers before anyone stores
+  __syncthreads();
+  if (active) reinterpret_cast<uint4*>(base + (size_t)(L + j) * row_bytes)[t] = v;
 }
 
 hipError_t launch_compact(const Dims& D, const RowMap& rm, const cerberus_state& st, const int* path, int batch,
                           hipStream_t s) {
-  hipLaunchKernelGGL(k_compact, dim3(D.n_layers * 2, D.nH, batch), dim3(64), 0, s, D, rm, st, path, D.dtype == 0 ? 4 : 2);
+  hipLaunchKernelGGL(k_compact, dim3(D.n_layers * 2, D.nH, batch), dim3(64, D.Hc), 0, s, D, rm, st, path,
+                     D.dtype == 0 ? 4 : 2);
   return hipGetLastError();
 }
 
@@ -446,27 +466,41 @@ hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const f
 // (value descending, id ascending).  Sequences whose gate chose the auto-regressive step keep
 // their old candidates.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_topk(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
-                                              int topk) {
-  __shared__ float shv[4];
-  __shared__ int shi[4];
+__global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
+                                               int topk) {
+  __shared__ float shv[16];
+  __shared__ int shi[16];
   const int i = blockIdx.x, b = blockIdx.y;
   if (st.gate_flag[b] != 0 || a.seq_T[b] <= 0) return;
   const float* lg = a.logits[i] + (size_t)b * V;
-  if (tp.head_logits)
-    for (int v = threadIdx.x; v < V; v += 256) tp.head_logits[((size_t)b * Hc + i) * V + v] = lg[v];
+  // every thread keeps its slice of the row in registers: float4 groups tid, tid + 1024, ...
+  constexpr int kG = 16;                       // up to 16 * 4096 = 65536 vocabulary entries per pass
+  float4 val[kG];
+#pragma unroll
+  for (int k = 0; k < kG; ++k) {
+    const int v = (k * 1024 + threadIdx.x) * 4;
+    val[k] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    if (v < V) {
+      val[k] = *reinterpret_cast<const float4*>(lg + v);
+      if (tp.head_logits) *reinterpret_cast<float4*>(tp.head_logits + ((size_t)b * Hc + i) * V + v) = val[k];
+    }
+  }
   float pv = INFINITY;
   int pi = -1;
-  for (int k = 0; k < topk; ++k) {
+  for (int r = 0; r < topk; ++r) {
     float bv = -INFINITY;
     int bi = INT_MAX;
-    for (int v = threadIdx.x; v < V; v += 256) {
-      const float val = lg[v];
-      if (val < pv || (val == pv && v > pi)) better(bv, bi, val, v);
+#pragma unroll
+    for (int k = 0; k < kG; ++k) {
+      const int v = (k * 1024 + threadIdx.x) * 4;
+      if (val[k].x < pv || (val[k].x == pv && v > pi)) better(bv, bi, val[k].x, v);
+      if (val[k].y < pv || (val[k].y == pv && v + 1 > pi)) better(bv, bi, val[k].y, v + 1);
+      if (val[k].z < pv || (val[k].z == pv && v + 2 > pi)) better(bv, bi, val[k].z, v + 2);
+      if (val[k].w < pv || (val[k].w == pv && v + 3 > pi)) better(bv, bi, val[k].w, v + 3);
     }
     block_argmax(bv, bi, shv, shi);
     if (bi == INT_MAX) bi = 0;
-    if (threadIdx.x == 0) st.cand[((size_t)b * Hc + i) * topk + k] = bi;
+    if (threadIdx.x == 0) st.cand[((size_t)b * Hc + i) * topk + r] = bi;
     pv = bv;
     pi = bi;
   }
@@ -474,7 +508,7 @@ __global__ __launch_bounds__(256) void k_topk(const TopkArgs a, const cerberus_s
 
 hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& st, const cerberus_taps& tp, int batch,
                        hipStream_t s) {
-  hipLaunchKernelGGL(k_topk, dim3(D.Hc, batch), dim3(256), 0, s, a, st, tp, D.V, D.Hc, D.topk);
+  hipLaunchKernelGGL(k_topk, dim3(D.Hc, batch), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.topk);
   return hipGetLastError();
 }
 
