@@ -79,7 +79,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 512, max_split = 8, gemm_nsub = 2, act_split = 1;
+  int use_mfma_attn = 1, target_wgs = 384, max_split = 8, gemm_nsub = 2, act_split = 1;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
   void* workspace = nullptr;
@@ -170,7 +170,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->attn = b.take<unsigned char>((size_t)planes * R64 * d * el);
   c->act = b.take<unsigned char>((size_t)planes * R64 * D.Fpad * el);
   const size_t nmax = (size_t)std::max(std::max(3 * d, 2 * D.F), D.V);
-  c->part_floats = 8 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
+  c->part_floats = 16 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
   c->part = b.take<float>(c->part_floats);
   const size_t slots = (size_t)B * D.nH * c->n_chunks_max * 64;
   c->attn_po = b.take<float>(slots * D.dh);
@@ -572,7 +572,7 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
     ctx->act_split = value;
     build_plans(ctx);
   } else if (n == "gemm_max_split") {
-    if (value < 1 || value > 8) return fail(CERBERUS_ERR_ARG, "gemm_max_split out of 1..8");
+    if (value < 1 || value > 16) return fail(CERBERUS_ERR_ARG, "gemm_max_split out of 1..16");
     ctx->max_split = value;
     build_plans(ctx);
   } else {

@@ -47,7 +47,10 @@ hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int K
 // loads stay in flight across chunk boundaries.
 // ---------------------------------------------------------------------------------------------
 constexpr int kLdsRow = 512;
-constexpr int kRing = 4;       // k-steps of weights in flight per wave
+#ifndef CERB_KRING
+#define CERB_KRING 4
+#endif
+constexpr int kRing = CERB_KRING;  // k-steps of weights in flight per wave
 
 __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
   if (g.skip_flags == nullptr) return false;
