@@ -44,10 +44,9 @@ def algorithmic_bytes(cfg: dict, T: int, L: int, elem: int = 2) -> dict:
     return out
 
 
-def cpu_baseline(cfg: dict, W_dev: dict, parent, rank, L: int, cap: int, n_sample_layers: int = 2) -> dict:
-    """Times the CPU oracle, as it stands, on a bounded sample of the same workload: the full
-    step (all tree nodes, LM head, gate, heads, top-k) with `n_sample_layers` of the decoder layers,
-    then scales the per-layer part to the full depth."""
+def cpu_baseline(cfg: dict, W_dev: dict, parent, rank, L: int, cap: int, reps: int = 2) -> dict:
+    """Times the CPU oracle, as it stands, on the same workload: `reps` whole steps (all layers, all
+    tree nodes, LM head, gate, heads, top-k) from the same seeded weights and KV prefix."""
     import numpy as np
     import torch
     from oracle import cerberus_oracle as orc
@@ -58,30 +57,36 @@ def cpu_baseline(cfg: dict, W_dev: dict, parent, rank, L: int, cap: int, n_sampl
     except Exception:
         threads = os.cpu_count() or 1
 
-    sub = dict(cfg, n_layers=n_sample_layers)
-    W = {k: synth.to_host_f32(v) for k, v in W_dev.items() if k != "layers"}
-    W["layers"] = [synth.to_host_f32(W_dev["layers"][l]) for l in range(n_sample_layers)]
-    kv_t = synth.make_kv_prefix(sub, 1, cap, seed=0, dtype=torch.bfloat16, device="cpu")
-    kv = [(kv_t[l, 0, 0].double().numpy(), kv_t[l, 1, 0].double().numpy()) for l in range(n_sample_layers)]
+    W = synth.to_host_f32(W_dev)
+    kv_t = synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda")
+    kv = [(kv_t[l, 0, 0].double().cpu().numpy(), kv_t[l, 1, 0].double().cpu().numpy()) for l in range(cfg["n_layers"])]
+    del kv_t
     root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
     cand = synth.make_candidates(cfg, 1, seed=3)[0].numpy()
-
-    def run(n_layers_used):
-        c = dict(sub, n_layers=n_layers_used)
-        st = orc.new_state([(K.copy(), V.copy()) for K, V in kv[:max(n_layers_used, 1)]], L, root, cand, 0)
+    times = []
+    for _ in range(reps):
+        st = orc.new_state(kv, L, root, cand, 0)      # rows >= L are rewritten by every step
         t0 = time.perf_counter()
-        orc.verify_step(c, W, parent, rank, st)
-        return time.perf_counter() - t0
+        orc.verify_step(cfg, W, parent, rank, st)
+        times.append(time.perf_counter() - t0)
+    return {"value": round(float(np.mean(times)) * 1e6, 1), "unit": "us/step", "cores": int(threads), "kind": "oracle",
+            "sample": f"{reps} whole verify steps of this workload (every layer and tree node, LM head, gate, heads, "
+                      f"top-k), mean of {', '.join(f'{t:.2f}' for t in times)} s",
+            "measured_s": round(float(np.sum(times)), 3)}
 
-    t_full = run(n_sample_layers)
-    t_rest = run(0)                       # embedding, LM head, gate, heads, top-k only
-    per_layer = max(t_full - t_rest, 0.0) / n_sample_layers
-    est = t_rest + per_layer * cfg["n_layers"]
-    return {"value": est * 1e6, "unit": "us/step", "cores": int(threads), "kind": "oracle",
-            "sample": f"full step with {n_sample_layers} of {cfg['n_layers']} decoder layers timed "
-                      f"({t_full:.2f} s) and without layers ({t_rest:.2f} s); per-layer time scaled to "
-                      f"{cfg['n_layers']} layers",
-            "measured_s": round(t_full + t_rest, 3)}
+
+def profiled_traffic_mb():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy), or None when no summary is there."""
+    path = os.path.join(ROOT, "profiles", "verify_step_7b_t64_l1024.txt")
+    try:
+        for line in open(path):
+            if line.startswith("average over all launches: fetch"):
+                parts = line.split()
+                return float(parts[5]) + float(parts[8])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
 
 
 def main() -> int:
@@ -223,14 +228,15 @@ def main() -> int:
         "step_hbm_frac": round(alg["total"] / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9), 4),
         "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2> (QKV, O, gate/up, down, LM head)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 else None),
+                     "traffic_unit": "MB per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, profiles/)",
+                     "algorithmic_MB_per_launch": round(tot_bytes / n_launch / 1e6, 1),
                      "avg_launch_us": round(tot_ms * 1e3 / n_launch, 2), "launches_per_step": n_launch,
                      "per_kind": gemm},
     }
-    if not args.no_cpu and name != "tiny":
+    if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, W, parent, rank, L, cap)
-    elif not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, W, parent, rank, L, cap, n_sample_layers=cfg["n_layers"])
     print(json.dumps(out))
     return 0
 
