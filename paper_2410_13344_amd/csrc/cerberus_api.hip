@@ -79,7 +79,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 384, max_split = 8, gemm_nsub = 2, act_split = 1;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
   void* workspace = nullptr;

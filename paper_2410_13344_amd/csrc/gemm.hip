@@ -48,7 +48,7 @@ hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int K
 // ---------------------------------------------------------------------------------------------
 constexpr int kLdsRow = 512;
 #ifndef CERB_KRING
-#define CERB_KRING 4
+#define CERB_KRING 8
 #endif
 constexpr int kRing = CERB_KRING;  // k-steps of weights in flight per wave
 
@@ -73,6 +73,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   const int split = local % P.S;
   const int ntile = local / P.S;
   constexpr int KSC = SPLIT ? 4 : 8;         // k-steps per LDS chunk
+  static_assert((2 * KSC) % kRing == 0 && (kRing % KSC == 0 || KSC % kRing == 0),
+                "ring slots must be compile-time constants: k-step (chunk parity * KSC + s) lives in slot of that index mod kRing");
   const int ksteps = P.K / 32;               // K is a multiple of 256
   const int ks0 = split * P.kps;             // kps is a multiple of 8
   const int ks1 = min(ks0 + P.kps, ksteps);
@@ -101,70 +103,95 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
 #pragma unroll
     for (int j = 0; j < NSUB; ++j) acc[mt][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  // activation chunk c+1 travels global -> registers while chunk c is consumed from LDS.
-  // (Plain unrolled loops with constant indices on purpose: staging arrays touched through a
-  // lambda end up in scratch memory, and a scratch round trip inside the loop serialises the whole
-  // in-order load queue.)
-  constexpr int kApt = MT * 2;  // 16-byte pieces per thread per chunk
-  const bf16_t* A = reinterpret_cast<const bf16_t*>(P.A);
-  const bf16_t* a_src[kApt];
-  int a_dst[kApt];
-#pragma unroll
-  for (int i = 0; i < kApt; ++i) {
-    const int idx = threadIdx.x + i * 256;
-    const int r = idx >> 5, pc = idx & 31;
-    a_src[i] = A + (size_t)(m0 + r) * P.lda + (size_t)ks0 * 32 +
-               (SPLIT ? (size_t)(pc >> 4) * P.lo_off + (pc & 15) * 8 : (size_t)pc * 8);
-    a_dst[i] = r * kLdsRow + ((pc ^ (r & 15)) * 16);
+  // Activation chunks travel global -> registers -> LDS two chunks ahead of their use: the loads of
+  // chunk c+2 are issued before chunk c is multiplied and are written to LDS after chunk c+1's
+  // buffer has been freed, so an L2 round trip (about three chunks of MFMA time) is covered.
+  // Thread t owns 16-byte piece t%32 of rows t/32 + 8i.  The staging registers are named scalars
+  // (P0..7 / Q0..7) on purpose: arrays that live across the loop back-edge, or are touched through
+  // a lambda, end up in scratch memory, and a scratch round trip inside the loop serialises the
+  // whole in-order load queue.
+  constexpr int kApt = MT * 2;  // pieces per thread per chunk
+  const int a_r0 = threadIdx.x >> 5, a_pc = threadIdx.x & 31;
+  const bf16_t* a_src = reinterpret_cast<const bf16_t*>(P.A) + (size_t)(m0 + a_r0) * P.lda + (size_t)ks0 * 32 +
+                        (SPLIT ? (size_t)(a_pc >> 4) * P.lo_off + (a_pc & 15) * 8 : (size_t)a_pc * 8);
+  const size_t a_step = (size_t)8 * P.lda;                 // row r0 + 8i
+  const int a_q = a_pc ^ (a_r0 & 15);                      // (r0 + 8i) & 15 flips bit 3 for odd i
+  const int a_dst_e = a_r0 * kLdsRow + a_q * 16, a_dst_o = a_r0 * kLdsRow + (a_q ^ 8) * 16;
+
+#define CERB_A_LD(X, CH)                                                                                      \
+  {                                                                                                           \
+    const bf16_t* sp = a_src + (size_t)(CH) * (KSC * 32);                                                     \
+    if (kApt > 0) X##0 = *reinterpret_cast<const uint4*>(sp);                                                 \
+    if (kApt > 1) X##1 = *reinterpret_cast<const uint4*>(sp + a_step);                                        \
+    if (kApt > 2) X##2 = *reinterpret_cast<const uint4*>(sp + 2 * a_step);                                    \
+    if (kApt > 3) X##3 = *reinterpret_cast<const uint4*>(sp + 3 * a_step);                                    \
+    if (kApt > 4) X##4 = *reinterpret_cast<const uint4*>(sp + 4 * a_step);                                    \
+    if (kApt > 5) X##5 = *reinterpret_cast<const uint4*>(sp + 5 * a_step);                                    \
+    if (kApt > 6) X##6 = *reinterpret_cast<const uint4*>(sp + 6 * a_step);                                    \
+    if (kApt > 7) X##7 = *reinterpret_cast<const uint4*>(sp + 7 * a_step);                                    \
   }
-  uint4 areg[kApt];
-#pragma unroll
-  for (int i = 0; i < kApt; ++i) areg[i] = *reinterpret_cast<const uint4*>(a_src[i]);
+#define CERB_A_ST(X, BUF)                                                                                     \
+  {                                                                                                           \
+    unsigned char* dp = lds + (BUF) * kBuf;                                                                   \
+    if (kApt > 0) *reinterpret_cast<uint4*>(dp + a_dst_e) = X##0;                                             \
+    if (kApt > 1) *reinterpret_cast<uint4*>(dp + a_dst_o + 8 * kLdsRow) = X##1;                               \
+    if (kApt > 2) *reinterpret_cast<uint4*>(dp + a_dst_e + 16 * kLdsRow) = X##2;                              \
+    if (kApt > 3) *reinterpret_cast<uint4*>(dp + a_dst_o + 24 * kLdsRow) = X##3;                              \
+    if (kApt > 4) *reinterpret_cast<uint4*>(dp + a_dst_e + 32 * kLdsRow) = X##4;                              \
+    if (kApt > 5) *reinterpret_cast<uint4*>(dp + a_dst_o + 40 * kLdsRow) = X##5;                              \
+    if (kApt > 6) *reinterpret_cast<uint4*>(dp + a_dst_e + 48 * kLdsRow) = X##6;                              \
+    if (kApt > 7) *reinterpret_cast<uint4*>(dp + a_dst_o + 56 * kLdsRow) = X##7;                              \
+  }
+
+  uint4 P0, P1, P2, P3, P4, P5, P6, P7, Q0, Q1, Q2, Q3, Q4, Q5, Q6, Q7;
+  P0 = P1 = P2 = P3 = P4 = P5 = P6 = P7 = Q0 = Q1 = Q2 = Q3 = Q4 = Q5 = Q6 = Q7 = make_uint4(0, 0, 0, 0);
+  CERB_A_LD(P, 0)
   uint4 ring[kRing][NSUB];
 #pragma unroll
   for (int i = 0; i < kRing; ++i)
 #pragma unroll
     for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + i, ks1 - 1) * 64];
-#pragma unroll
-  for (int i = 0; i < kApt; ++i) *reinterpret_cast<uint4*>(lds + a_dst[i]) = areg[i];
+  CERB_A_ST(P, 0)
+  CERB_A_LD(P, min(1, nchunks - 1))
   __syncthreads();
 
   const int a_row = lane & 15, a_grp = lane >> 4;  // (mt*16 + a_row) & 15 == a_row
-  for (int c = 0; c < nchunks; ++c) {
-    const int cn = min(c + 1, nchunks - 1);
-#pragma unroll
-    for (int i = 0; i < kApt; ++i) areg[i] = *reinterpret_cast<const uint4*>(a_src[i] + (size_t)cn * (KSC * 32));
-    const unsigned char* L = lds + (c & 1) * kBuf + a_row * kLdsRow;
-    const int kb = ks0 + c * KSC;
-#pragma unroll
-    for (int s = 0; s < KSC; ++s) {
-      uint4 b[NSUB];
-#pragma unroll
-      for (int j = 0; j < NSUB; ++j) {
-        b[j] = ring[s % kRing][j];
-        ring[s % kRing][j] = wp[j][(size_t)min(kb + s + kRing, ks1 - 1) * 64];
-      }
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((s * 4 + a_grp) ^ a_row) * 16));
-#pragma unroll
-        for (int j = 0; j < NSUB; ++j)
-          acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                               __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);
-        if (SPLIT) {
-          const uint4 al = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((16 + s * 4 + a_grp) ^ a_row) * 16));
-#pragma unroll
-          for (int j = 0; j < NSUB; ++j)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, al),
-                                                                 __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);
-        }
-      }
-    }
-    unsigned char* Ln = lds + ((c + 1) & 1) * kBuf;
-#pragma unroll
-    for (int i = 0; i < kApt; ++i) *reinterpret_cast<uint4*>(Ln + a_dst[i]) = areg[i];
-    __syncthreads();
+
+#define CERB_GEMM_CHUNK(C, PAR, NEXT2, NEXT1)                                                                                \
+  {                                                                                                                       \
+    CERB_A_LD(NEXT2, min((C) + 2, nchunks - 1))                                                                           \
+    const unsigned char* L = lds + ((C) & 1) * kBuf + a_row * kLdsRow;                                                    \
+    const int kb = ks0 + (C) * KSC;                                                                                       \
+    _Pragma("unroll") for (int s = 0; s < KSC; ++s) {                                                                     \
+      uint4 b[NSUB];                                                                                                      \
+      _Pragma("unroll") for (int j = 0; j < NSUB; ++j) {                                                                  \
+        b[j] = ring[((PAR) * KSC + s) % kRing][j];                                                                        \
+        ring[((PAR) * KSC + s) % kRing][j] = wp[j][(size_t)min(kb + s + kRing, ks1 - 1) * 64];                            \
+      }                                                                                                                   \
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                                 \
+        const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((s * 4 + a_grp) ^ a_row) * 16));        \
+        _Pragma("unroll") for (int j = 0; j < NSUB; ++j) acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(            \
+            __builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);                    \
+        if (SPLIT) {                                                                                                      \
+          const uint4 al =                                                                                                \
+              *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((16 + s * 4 + a_grp) ^ a_row) * 16));             \
+          _Pragma("unroll") for (int j = 0; j < NSUB; ++j) acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(          \
+              __builtin_bit_cast(bf16x8_t, al), __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);                 \
+        }                                                                                                                 \
+      }                                                                                                                   \
+    }                                                                                                                     \
+    CERB_A_ST(NEXT1, ((C) + 1) & 1)                                                                                       \
+    __syncthreads();                                                                                                      \
   }
+
+  for (int c = 0; c < nchunks; c += 2) {
+    CERB_GEMM_CHUNK(c, 0, Q, P)               // P holds chunk c+1, Q receives chunk c+2
+    if (c + 1 >= nchunks) break;              // uniform over the workgroup
+    CERB_GEMM_CHUNK(c + 1, 1, P, Q)           // Q holds chunk c+2, P receives chunk c+3
+  }
+#undef CERB_GEMM_CHUNK
+#undef CERB_A_LD
+#undef CERB_A_ST
 
   // D layout: lane holds column lane%16, rows 4*(lane/16) + v
   float* out = P.out + (size_t)split * P.out_rows * P.N;
