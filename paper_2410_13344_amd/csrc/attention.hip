@@ -31,11 +31,27 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
     o[e] = 0.f;
   }
   float m = -INFINITY, l = 0.f;
+  const int row0 = a.rm.seq_row0[b];
+  const T* Kt = reinterpret_cast<const T*>(a.ktree);
+  const T* Vt = reinterpret_cast<const T*>(a.vtree);
   for (int p = 0; p < L + Tb; ++p) {
     if (p >= L && !((mask >> (p - L)) & 1ull)) continue;
+    const bool side = Kt != nullptr && p >= L;    // this step's rows at hi + lo precision
+    const size_t so = (size_t)(row0 + p - L) * a.nH * dh + h * dh;
+    float kv[EPL], vv[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      if (side) {
+        kv[e] = ld_f(Kt + so + lane + 64 * e) + ld_f(Kt + a.q_lo_off + so + lane + 64 * e);
+        vv[e] = ld_f(Vt + so + lane + 64 * e) + ld_f(Vt + a.q_lo_off + so + lane + 64 * e);
+      } else {
+        kv[e] = ld_f(Kb + (size_t)p * dh + lane + 64 * e);
+        vv[e] = ld_f(Vb + (size_t)p * dh + lane + 64 * e);
+      }
+    }
     float s = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) s += qv[e] * ld_f(Kb + (size_t)p * dh + lane + 64 * e);
+    for (int e = 0; e < EPL; ++e) s += qv[e] * kv[e];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     const float mn = fmaxf(m, s);
@@ -43,7 +59,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
     const float pw = expf(s - mn);
     l = l * corr + pw;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) o[e] = o[e] * corr + pw * ld_f(Vb + (size_t)p * dh + lane + 64 * e);
+    for (int e = 0; e < EPL; ++e) o[e] = o[e] * corr + pw * vv[e];
     m = mn;
   }
   T* out = reinterpret_cast<T*>(a.out) + (size_t)r * a.nH * dh + h * dh;
@@ -72,25 +88,49 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char sK[CK * ROWB];
   __shared__ __attribute__((aligned(16))) unsigned char sV[CK * ROWB];
 
-  const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.y, b = blockIdx.z;
   const int L = a.rm.seq_L[b], Tb = a.rm.seq_T[b], row0 = a.rm.seq_row0[b];
-  const int NK = L + Tb;
+  if (Tb <= 0) return;
+  // The last workgroup of a (head, sequence) takes the tree chunk: the step's own <= 64 rows, read
+  // from the hi + lo side planes (LDS rows 0..63 = hi, 64..127 = lo of the same key).  The others
+  // take 128 committed cache rows each.
+  const bool tree = blockIdx.x == gridDim.x - 1;
+  const int nprefix = (L + CK - 1) / CK;
+  if (!tree && (int)blockIdx.x >= nprefix) return;
+  const int c = tree ? nprefix : blockIdx.x;      // partial slot
   const int key0 = c * CK;
-  if (Tb <= 0 || key0 >= NK) return;
 
-  const bf16_t* Kg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap * DH;
-  const bf16_t* Vg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap * DH;
-  for (int i = threadIdx.x; i < CK * PPR; i += 256) {
-    const int key = i / PPR, pc = i % PPR;
-    const int kabs = key0 + key;
-    uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-    if (kabs < NK) {
-      kk = reinterpret_cast<const uint4*>(Kg + (size_t)kabs * DH)[pc];
-      vv = reinterpret_cast<const uint4*>(Vg + (size_t)kabs * DH)[pc];
+  if (tree) {
+    const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.ktree) + (size_t)row0 * a.nH * DH + h * DH;
+    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(a.vtree) + (size_t)row0 * a.nH * DH + h * DH;
+    for (int i = threadIdx.x; i < CK * PPR; i += 256) {
+      const int key = i / PPR, pc = i % PPR;
+      const int m = key & 63;                     // tree node
+      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (m < Tb) {
+        const size_t off = (size_t)m * a.nH * DH + (key >= 64 ? a.q_lo_off : 0);
+        kk = reinterpret_cast<const uint4*>(Kt + off)[pc];
+        vv = reinterpret_cast<const uint4*>(Vt + off)[pc];
+      }
+      const int sw = pc ^ (key & (PPR - 1));
+      *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = kk;
+      *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = vv;
     }
-    const int sw = pc ^ (key & (PPR - 1));
-    *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = kk;
-    *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = vv;
+  } else {
+    const bf16_t* Kg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap * DH;
+    const bf16_t* Vg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap * DH;
+    for (int i = threadIdx.x; i < CK * PPR; i += 256) {
+      const int key = i / PPR, pc = i % PPR;
+      const int kabs = key0 + key;
+      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (kabs < L) {
+        kk = reinterpret_cast<const uint4*>(Kg + (size_t)kabs * DH)[pc];
+        vv = reinterpret_cast<const uint4*>(Vg + (size_t)kabs * DH)[pc];
+      }
+      const int sw = pc ^ (key & (PPR - 1));
+      *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = kk;
+      *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = vv;
+    }
   }
   __syncthreads();
 
@@ -110,7 +150,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   const float scale = rsqrtf((float)DH);
 
   float s[CK / 16][4];
-  float m = -INFINITY;
 #pragma unroll
   for (int kt = 0; kt < CK / 16; ++kt) {
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
@@ -125,14 +164,24 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
                                                     acc, 0, 0, 0);
     }
 #pragma unroll
+    for (int v = 0; v < 4; ++v) s[kt][v] = acc[v];
+  }
+  if (tree) {   // LDS rows 64.. hold the lo halves of keys 0..63: their products belong to the same scores
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) s[kt][v] += s[kt + 4][v];
+  }
+  float m = -INFINITY;
+#pragma unroll
+  for (int kt = 0; kt < CK / 16; ++kt)
+#pragma unroll
     for (int v = 0; v < 4; ++v) {
-      const int kabs = key0 + kt * 16 + 4 * g + v;
-      bool vis = kabs < L;
-      if (!vis && kabs < NK) vis = (amask >> (kabs - L)) & 1ull;
-      s[kt][v] = (vis && qvalid) ? acc[v] * scale : -INFINITY;
+      const int kin = kt * 16 + 4 * g + v;   // key within the chunk
+      const bool vis = tree ? (kt < 4 && ((amask >> (kin & 63)) & 1ull)) : (key0 + kin < L);
+      s[kt][v] = (vis && qvalid) ? s[kt][v] * scale : -INFINITY;
       m = fmaxf(m, s[kt][v]);
     }
-  }
   m = fmaxf(m, __shfl_xor(m, 16, 64));
   m = fmaxf(m, __shfl_xor(m, 32, 64));
   const float msafe = (m == -INFINITY) ? 0.f : m;
@@ -147,6 +196,12 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     }
   lsum += __shfl_xor(lsum, 16, 64);
   lsum += __shfl_xor(lsum, 32, 64);
+  if (tree) {   // the lo halves of the V rows take the same probabilities
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) s[kt + 4][v] = s[kt][v];
+  }
 
   f32x4_t o[DT];
 #pragma unroll
@@ -196,8 +251,7 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
   const int r = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
   if (r >= *a.rm.n_rows) return;
   const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
-  const int NK = a.rm.seq_L[b] + a.rm.seq_T[b];
-  const int nch = (NK + 127) / 128;
+  const int nch = (a.rm.seq_L[b] + 127) / 128 + 1;   // committed-row chunks + the tree chunk
   const size_t base = (((size_t)b * a.nH + h) * a.n_chunks_max) * 64 + node;
   float M = -INFINITY;
   for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[(base + (size_t)c * 64) * 2]);
@@ -223,7 +277,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, int use_mfma, hipStrea
     }
     return hipGetLastError();
   }
-  dim3 grid(a.n_chunks_max, a.nH, a.batch);
+  dim3 grid(a.n_chunks_max, a.nH, a.batch);   // n_chunks_max = ceil(cap / 128) + 1: the last block is the tree chunk
   dim3 cgrid(a.rows_max, a.nH);
   if (a.dh == 64) {
     hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(256), 0, s, a);

@@ -59,10 +59,10 @@ struct cerberus_ctx {
   // device memory, all inside the workspace
   TreeDev tree{};
   RowMap rm{};
-  float* inv_freq = nullptr;
+  double* inv_freq = nullptr;
   int *last_row = nullptr, *path = nullptr, *g = nullptr;
   float *x = nullptr, *h_last = nullptr, *part = nullptr, *attn_po = nullptr, *attn_ml = nullptr;
-  void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+  void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr, *ktree = nullptr, *vtree = nullptr;
   void* hsA[2] = {nullptr, nullptr};
   float* hsF[2] = {nullptr, nullptr};
   float* final_norm = nullptr;
@@ -136,7 +136,7 @@ void fill_dims(cerberus_ctx* c, const cerberus_config* cfg, const cerberus_tree*
   c->elem = cfg->dtype == CERBERUS_F32 ? 4 : 2;
   c->R64 = (int)align_up((size_t)cfg->max_batch * t->n_nodes, 64);
   D.R64 = c->R64;
-  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128);
+  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128) + 1;  // committed-row chunks + the tree chunk
 }
 
 // Assigns every workspace pointer of the context; with base == nullptr it only measures.
@@ -150,7 +150,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->tree.rank = b.take<int>(T);
   c->tree.depth = b.take<int>(T);
   c->tree.anc = b.take<unsigned long long>(T);
-  c->inv_freq = b.take<float>(D.dh / 2);
+  c->inv_freq = b.take<double>(D.dh / 2);
   c->rm.n_rows = b.take<int>(1);
   c->rm.seq_row0 = b.take<int>(B);
   c->rm.seq_T = b.take<int>(B);
@@ -168,6 +168,12 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->xn = b.take<unsigned char>((size_t)planes * R64 * d * el);
   c->q = b.take<unsigned char>((size_t)planes * R64 * d * el);
   c->attn = b.take<unsigned char>((size_t)planes * R64 * d * el);
+  if (cfg.dtype == CERBERUS_BF16) {  // this step's K/V rows as hi + lo planes (the cache keeps one bf16)
+    c->ktree = b.take<unsigned char>((size_t)2 * R64 * d * el);
+    c->vtree = b.take<unsigned char>((size_t)2 * R64 * d * el);
+  } else {
+    c->ktree = c->vtree = nullptr;
+  }
   c->act = b.take<unsigned char>((size_t)planes * R64 * D.Fpad * el);
   const size_t nmax = (size_t)std::max(std::max(3 * d, 2 * D.F), D.V);
   c->part_floats = 16 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
@@ -317,9 +323,10 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
     TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
     const GemmProb& pq = c->p_qkv[l].p[0];
     void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
-    HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, rows_max, s));
+    HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, c->ktree, c->vtree,
+                           rows_max, s));
     AttnArgs aa{};
-    aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
+    aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
     aa.anc = c->tree.anc; aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
     aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
@@ -419,8 +426,8 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
     if (n > 0) { c->depth[n] = c->depth[c->parent[n]] + 1; c->anc[n] = c->anc[c->parent[n]]; }
     c->anc[n] |= 1ull << n;
   }
-  std::vector<float> inv(D.dh / 2);
-  for (int j = 0; j < D.dh / 2; ++j) inv[j] = (float)std::pow((double)cfg->rope_theta, -2.0 * j / D.dh);
+  std::vector<double> inv(D.dh / 2);
+  for (int j = 0; j < D.dh / 2; ++j) inv[j] = std::pow((double)cfg->rope_theta, -2.0 * j / D.dh);
 
   auto cleanup = [&](int rc) { delete c; return rc; };
 #define HIP_INIT(expr)                                                                                      \
@@ -435,7 +442,7 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   HIP_INIT(hipMemcpy((void*)c->tree.rank, c->rank.data(), T * sizeof(int), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy((void*)c->tree.depth, c->depth.data(), T * sizeof(int), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy((void*)c->tree.anc, c->anc.data(), T * sizeof(unsigned long long), hipMemcpyHostToDevice));
-  HIP_INIT(hipMemcpy(c->inv_freq, inv.data(), inv.size() * sizeof(float), hipMemcpyHostToDevice));
+  HIP_INIT(hipMemcpy(c->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice));
 
   hipStream_t s0 = nullptr;
   HIP_INIT(launch_to_f32(w->final_norm, c->final_norm, d, D.dtype, s0));

@@ -95,9 +95,11 @@ struct AttnArgs {
   const void* q;     // [rows][nH*dh]; bf16: lo plane q_lo_off elements later (0 in fp32 mode)
   size_t q_lo_off;
   const void* kv;    // layer base: [2][Bmax][nH][cap][dh]
+  const void* ktree; // bf16 mode: this step's K rows as hi + lo planes [rows][nH*dh] (lo plane q_lo_off later);
+  const void* vtree; //            the tree keys are read from here, the cache only serves rows < L
   void* out;         // [rows][nH*dh] attention output (GEMM A operand; bf16: lo plane out_lo_off elements later)
   size_t out_lo_off;
-  float* part_o;     // [B][nH][n_chunks_max][64][dh]
+  float* part_o;     // [B][nH][n_chunks_max][64][dh]; slot ceil(L/128) of a (seq, head) holds the tree chunk
   float* part_ml;    // [B][nH][n_chunks_max][64][2]
   RowMap rm;
   const unsigned long long* anc;

@@ -32,7 +32,8 @@ hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, floa
 hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s);
 hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
-                          const float* inv_freq, void* q, void* kv_layer, int rows_max, hipStream_t s);
+                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, int rows_max,
+                          hipStream_t s);
 hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
                          int rows_max, hipStream_t s);
 hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, int* g,

@@ -185,8 +185,9 @@ hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const f
 // attention kernel and k, v into the cache at row L + node.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const float* __restrict__ inv_freq,
-                          const RowMap rm, T* __restrict__ q, size_t q_lo_off, T* __restrict__ kv_layer, const Dims D) {
+__global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const double* __restrict__ inv_freq,
+                          const RowMap rm, T* __restrict__ q, size_t q_lo_off, T* __restrict__ kv_layer,
+                          T* __restrict__ ktree, T* __restrict__ vtree, const Dims D) {
   const int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
   if (r >= *rm.n_rows) return;
   const int b = rm.row_seq[r], node = rm.row_node[r];
@@ -197,27 +198,41 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
     const float* p = part + s * pstride + (size_t)r * N;
     v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
   }
-  float sn, cs;
-  sincosf((float)rm.row_pos[r] * inv_freq[j], &sn, &cs);
+  // the angle in double: at position ~4000 an fp32 product is already off by 1e-4 rad
+  double snd, csd;
+  sincos((double)rm.row_pos[r] * inv_freq[j], &snd, &csd);
+  const float sn = (float)snd, cs = (float)csd;
   st_a(q + (size_t)r * d + c0, q_lo_off, v[0] * cs - v[1] * sn);
   st_a(q + (size_t)r * d + c1, q_lo_off, v[0] * sn + v[1] * cs);
+  const float k0 = v[2] * cs - v[3] * sn, k1 = v[2] * sn + v[3] * cs;
   const size_t row = (size_t)(rm.seq_L[b] + node);
   T* Kr = kv_layer + (((size_t)(0 * D.Bmax + b) * D.nH + h) * D.cap + row) * dh;
   T* Vr = kv_layer + (((size_t)(1 * D.Bmax + b) * D.nH + h) * D.cap + row) * dh;
-  st_f(Kr + j, v[2] * cs - v[3] * sn);
-  st_f(Kr + j + half, v[2] * sn + v[3] * cs);
+  st_f(Kr + j, k0);
+  st_f(Kr + j + half, k1);
   st_f(Vr + j, v[4]);
   st_f(Vr + j + half, v[5]);
+  if (ktree) {
+    // This step's attention reads the tree rows from these hi+lo planes instead: rounding a new
+    // row to one bf16 before its own step uses it is the largest single error of the bf16 path
+    // (4.8e-2 of logits at the 13B shape against 1e-2 from everything else).
+    st_a(ktree + (size_t)r * d + c0, q_lo_off, k0);
+    st_a(ktree + (size_t)r * d + c1, q_lo_off, k1);
+    st_a(vtree + (size_t)r * d + c0, q_lo_off, v[4]);
+    st_a(vtree + (size_t)r * d + c1, q_lo_off, v[5]);
+  }
 }
 
 hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
-                          const float* inv_freq, void* q, void* kv_layer, int rows_max, hipStream_t s) {
+                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, int rows_max,
+                          hipStream_t s) {
   dim3 grid(rows_max, D.nH), block(D.dh / 2);
   if (D.dtype == 0)
-    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (size_t)0, (float*)kv_layer, D);
+    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (size_t)0,
+                       (float*)kv_layer, (float*)nullptr, (float*)nullptr, D);
   else
     hipLaunchKernelGGL((k_rope_kv<bf16_t>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (bf16_t*)q,
-                       (size_t)D.R64 * D.d, (bf16_t*)kv_layer, D);
+                       (size_t)D.R64 * D.d, (bf16_t*)kv_layer, (bf16_t*)ktree, (bf16_t*)vtree, D);
   return hipGetLastError();
 }
 

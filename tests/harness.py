@@ -27,6 +27,9 @@ class Tol:
 TOL_F32 = Tol(logits=5e-5, hidden=5e-5, entropy=1e-5, kv_atol=2e-5, kv_rtol=2e-5)
 # bf16 GPU vs float64 oracle: 2e-2 max-abs on logits is the bar of the benchmark spec
 TOL_BF16 = Tol(logits=2e-2, hidden=3e-2, entropy=3e-2, kv_atol=3e-2, kv_rtol=2e-2)
+# the two-layer tiny model amplifies nothing: with hi+lo bf16 GEMM inputs its logits sit within 2e-4
+# of the oracle, so the tiny-shape tests use a ten times tighter bar (more integer decisions checked)
+TOL_BF16_TINY = Tol(logits=2e-3, hidden=4e-3, entropy=2e-3, kv_atol=3e-2, kv_rtol=2e-2)
 
 
 def torch_dtype(dtype: int):
@@ -89,9 +92,10 @@ class StepReport:
 
 
 def compare_step(cfg: dict, out: dict, st: B.DeviceState, taps: B.DeviceTaps, b: int, T_full: int, dtype: int,
-                 ost_after: dict, forced_argmax: bool = False) -> StepReport:
+                 ost_after: dict, forced_argmax: bool = False, tol: Optional[Tol] = None,
+                 check_status: bool = True) -> StepReport:
     """`out`: what the oracle's verify_step returned; `ost_after`: oracle state after the step."""
-    tol = tol_for(dtype)
+    tol = tol or tol_for(dtype)
     rep = StepReport()
     T = out["T"]
     Hc, K, V = cfg["n_cerb_heads"], cfg["topk"], cfg["vocab"]
@@ -178,7 +182,7 @@ def compare_step(cfg: dict, out: dict, st: B.DeviceState, taps: B.DeviceTaps, b:
                                 bad(f"candidate head {i} rank {j}: {cand[i, j]} vs {out['cand'][i, j]}")
                         else:
                             rep.cand_skipped += 1
-    status = int(st.status[0])
+    status = int(st.status[0]) if check_status else 0
     if status != 0:
         bad(f"device status word {status}")
     return rep
@@ -188,13 +192,16 @@ class Pair:
     """An oracle model and a device engine built from the same seeded weights."""
 
     def __init__(self, name: str, dtype: int, tree: str, seed: int = 0, max_batch: int = 1, kv_capacity: int = 256,
-                 lazy_host: bool = False, **overrides):
+                 lazy_host: bool = False, share: Optional["Pair"] = None, **overrides):
         self.cfg = synth.make_config(name, **overrides)
         self.dtype = dtype
         self.parent, self.rank = synth.make_tree(tree, self.cfg["n_cerb_heads"])
         self.T = len(self.parent)
-        self.W_dev = synth.make_weights(self.cfg, seed=seed, dtype=torch_dtype(dtype), device="cuda")
-        self.W = synth.to_host_lazy(self.W_dev) if lazy_host else synth.to_host_f32(self.W_dev)
+        if share is not None:                 # same seeded weights (device and host views), another engine
+            self.W_dev, self.W = share.W_dev, share.W
+        else:
+            self.W_dev = synth.make_weights(self.cfg, seed=seed, dtype=torch_dtype(dtype), device="cuda")
+            self.W = synth.to_host_lazy(self.W_dev) if lazy_host else synth.to_host_f32(self.W_dev)
         self.engine = B.Engine(self.cfg, self.W_dev, self.parent, self.rank, dtype, max_batch, kv_capacity)
         self.kv_capacity = kv_capacity
         self.max_batch = max_batch

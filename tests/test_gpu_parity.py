@@ -70,7 +70,8 @@ def _run_forced_steps(pair, n_steps, cand_mode, attn_mfma, gate_states=None):
         out = pair.oracle_step(ost, forced_gate_hidden=forced)
         pair.engine.verify_step(st, 1)
         torch.cuda.synchronize()
-        rep = H.compare_step(cfg, out, st, taps, 0, pair.T, dtype, ost)
+        rep = H.compare_step(cfg, out, st, taps, 0, pair.T, dtype, ost,
+                             tol=H.TOL_BF16_TINY if dtype == BF16 else None)
         say(f"  step {step}: T={out['T']} a={out['accept_len']} flag={out['flag']} logit_err={rep.max_logit_err:.2e} "
             f"h_err={rep.max_hidden_err:.2e} head_err={rep.max_head_logit_err:.2e} S_err={rep.entropy_err:.2e} "
             f"argmax {rep.argmax_checked}/{rep.argmax_checked + rep.argmax_skipped} cand {rep.cand_checked}/"
@@ -220,17 +221,76 @@ def test_bad_arguments_are_rejected(tiny_pairs):
         pair.engine.set_param("no_such_knob", 1)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_tiny_batch_mixed_ar_and_tree_in_one_launch(dtype):
+    """Four independent sequences with different prefix lengths and gate decisions share one launch:
+    rows are packed per sequence, a flagged sequence contributes a single row."""
+    pair = H.Pair("tiny", dtype, "tiny", seed=0, max_batch=4, kv_capacity=256)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    tol = H.TOL_BF16_TINY if dtype == BF16 else None
+    osts = []
+    for b, (n_prompt, flag) in enumerate(((40, 0), (77, 1), (128, 0), (100, 1))):
+        prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=20 + b).numpy()
+        ost = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+        if flag:
+            ost["flag"] = 1
+        osts.append(ost)
+    for step in range(4):
+        for b, ost in enumerate(osts):
+            H.round_oracle_kv(ost, dtype)
+            H.upload_sequence(st, b, ost, dtype)
+        outs = [pair.oracle_step(ost) for ost in osts]
+        pair.engine.verify_step(st, 4)
+        torch.cuda.synchronize()
+        assert int(st.status[0]) == 0
+        for b, (ost, out) in enumerate(zip(osts, outs)):
+            rep = H.compare_step(cfg, out, st, taps, b, pair.T, dtype, ost, tol=tol)
+            say(f"  step {step} seq {b}: T={out['T']} L={out['L_before']} a={out['accept_len']} logit_err={rep.max_logit_err:.2e}")
+            assert not rep.failures, f"step {step} seq {b}: " + "; ".join(rep.failures)
+        if step == 1:                      # flip the gate decisions for the next launch
+            for ost in osts:
+                ost["flag"] = 1 - ost["flag"]
+    # a batch smaller than max_batch and the forced one-token entry point
+    for b, ost in enumerate(osts[:3]):
+        H.round_oracle_kv(ost, dtype)
+        H.upload_sequence(st, b, ost, dtype)
+    outs = [pair.oracle_step(ost, force_ar=True) for ost in osts[:3]]
+    pair.engine.ar_step(st, 3)
+    torch.cuda.synchronize()
+    for b, (ost, out) in enumerate(zip(osts[:3], outs)):
+        rep = H.compare_step(cfg, out, st, taps, b, pair.T, dtype, ost, tol=tol)
+        assert out["T"] == 1 and not rep.failures, f"ar seq {b}: " + "; ".join(rep.failures)
+
+
 # ---------------------------------------------------------------------------------------------
 # full size: the 7B shape in the launch configuration bench.py times (bf16, 64-node tree, prefix
 # 1024).  The oracle cannot afford all 64 nodes, so it runs one sampled root-to-leaf path as a chain
 # tree: a node's result depends only on the prefix and its ancestors, so the chain's rows must equal
 # the corresponding rows of the full tree pass.
 # ---------------------------------------------------------------------------------------------
-def test_7b_full_size_sampled_path_matches_oracle():
-    L, cap = 1024, 1280
+@pytest.fixture(scope="module")
+def pair_7b():
     say("7B: building weights and engine")
-    pair = H.Pair("7b", BF16, "p63", seed=0, max_batch=1, kv_capacity=cap, lazy_host=True)
+    return H.Pair("7b", BF16, "p63", seed=0, max_batch=1, kv_capacity=1280, lazy_host=True)
+
+
+def test_7b_full_size_sampled_path_matches_oracle(pair_7b):
+    _full_size_sampled_path(pair_7b, 1024, 1280)
+
+
+def test_13b_full_size_sampled_path_matches_oracle():
+    """configs[3]: 40 layers, d 5120, 40 heads, FFN 13824, five decoding heads, prefix 2048."""
+    say("13B: building weights and engine")
+    pair = H.Pair("13b", BF16, "p63", seed=0, max_batch=1, kv_capacity=2304, lazy_host=True)
+    _full_size_sampled_path(pair, 2048, 2304)
+    pair.engine.close()
+
+
+def _full_size_sampled_path(pair, L, cap):
     cfg, T, tol = pair.cfg, pair.T, H.TOL_BF16
+    tag = f"{cfg['n_layers']}x{cfg['d_model']}"
     assert T == 64
     st = pair.engine.new_state()
     st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
@@ -267,7 +327,7 @@ def test_7b_full_size_sampled_path_matches_oracle():
     pair.engine.verify_step(st, 1)
     torch.cuda.synchronize()
     assert int(st.status[0]) == 0
-    say("7B: device step done; running the oracle on the sampled chain " + str(nodes))
+    say(tag + ": device step done; running the oracle on the sampled chain " + str(nodes))
 
     kv_host = [(kv_before[l, 0, 0].double().cpu().numpy(), kv_before[l, 1, 0].double().cpu().numpy())
                for l in range(cfg["n_layers"])]
@@ -282,13 +342,13 @@ def test_7b_full_size_sampled_path_matches_oracle():
     logits = taps.logits[idx].double().cpu().numpy()
     err = float(np.max(np.abs(logits - out["logits"])))
     herr = float(np.max(np.abs(taps.h_last[idx].double().cpu().numpy() - out["h_last"])))
-    say(f"7B: logits max-abs err {err:.3e} (std of logits {out['logits'].std():.3f}), h_last err {herr:.3e}")
+    say(f"{tag}: logits max-abs err {err:.3e} (std of logits {out['logits'].std():.3f}), h_last err {herr:.3e}")
     assert err <= tol.logits
     srt = -np.sort(-out["logits"], axis=1)
     safe = (srt[:, 0] - srt[:, 1]) > 2 * tol.logits
     g_real = np.argmax(out["logits"], axis=1)
     assert np.array_equal(taps.node_argmax[idx].cpu().numpy()[safe], g_real[safe])
-    say(f"7B: argmax checked on {int(safe.sum())}/{len(nodes)} nodes")
+    say(f"{tag}: argmax checked on {int(safe.sum())}/{len(nodes)} nodes")
 
     a = int(st.accept_len[0])
     assert a == len(nodes)
@@ -305,12 +365,12 @@ def test_7b_full_size_sampled_path_matches_oracle():
     assert torch.equal(st.kv[:, :, :, :, :L], kv_before[:, :, :, :, :L])
 
     S_gpu = float(st.entropy[0])
-    say(f"7B: entropy {S_gpu:.5f} vs {out['entropy']:.5f}")
+    say(f"{tag}: entropy {S_gpu:.5f} vs {out['entropy']:.5f}")
     assert abs(S_gpu - out["entropy"]) <= tol.entropy and int(st.gate_flag[0]) == 0
     hl = taps.head_logits[0].double().cpu().numpy()
     want = np.stack(out["head_logits"])
     herr2 = float(np.max(np.abs(hl - want)))
-    say(f"7B: head logits max-abs err {herr2:.3e} (std {want.std():.3f})")
+    say(f"{tag}: head logits max-abs err {herr2:.3e} (std {want.std():.3f})")
     K = cfg["topk"]
     cand_gpu = st.cand[0].cpu().numpy()
     checked = 0
@@ -322,4 +382,132 @@ def test_7b_full_size_sampled_path_matches_oracle():
             if H._margin_ok(s, j, tol_i):
                 checked += 1
                 assert cand_gpu[i, j] == out["cand"][i, j], (i, j)
-    say(f"7B: candidates checked {checked}/{cfg['n_cerb_heads'] * K}")
+    say(f"{tag}: candidates checked {checked}/{cfg['n_cerb_heads'] * K}")
+
+
+# ---------------------------------------------------------------------------------------------
+# configs[2]: 256 consecutive steps at the 7B shape with the gate active.  The oracle cannot run
+# 256 full-size steps, so the schedule is driven through the taps (forced gate input, forced
+# per-node argmax) and everything that is decided by small integer logic is checked against the
+# oracle's own functions on the same forced inputs: the gate decision of every step, the tree size
+# each step ran with, accepted path, committed tokens, next root and the growth of the cache length.
+# ---------------------------------------------------------------------------------------------
+def test_7b_gated_256_step_schedule(pair_7b):
+    L0, cap, n_steps, thr = 1024, 2560, 256, 9.0
+    pair = H.Pair("7b", BF16, "p63", max_batch=1, kv_capacity=cap, share=pair_7b, entropy_threshold=thr)
+    cfg, T, Hc = pair.cfg, pair.T, pair.cfg["n_cerb_heads"]
+    d = cfg["d_model"]
+    taps = pair.taps(logits=False, forced_argmax=True, forced_gate=True)
+    st = pair.engine.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
+    st.kv_len[0] = L0
+    st.root_token[0] = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    st.cand[0] = synth.make_candidates(cfg, 1, seed=3)[0].cuda()
+    st.gate_flag[0] = 0
+    rng = np.random.default_rng(11)
+    z = synth.make_gate_states(n_steps, d, seed=5, lo=1.0, hi=1.0).numpy()       # unit-scale states
+    depth, _ = orc.tree_tables(pair.parent)
+    children = {n: [c for c in range(T) if pair.parent[c] == n] for n in range(T)}
+    L, flag = L0, 0
+    n_ar = n_tree = committed = 0
+    for step in range(n_steps):
+        ar_next = rng.random() < 0.3                    # ~30 % of the steps hand over to an AR step
+        alpha = 0.5 if ar_next else 3.0                 # entropy ~11.8 bits vs ~5.5 bits around T = 9
+        hidden = (alpha * z[step]).astype(np.float32)
+        S_want, flag_want = orc.gate(hidden, thr)
+        assert flag_want == int(ar_next)
+        a_want = int(rng.integers(1, Hc + 2))           # accepted length drawn uniformly from 1..Hc+1
+        T_step = 1 if flag else T
+        # plant a path of that depth in the forced argmax (clipped to what this step's tree has)
+        tok = taps.node_token                           # filled by the step itself; read after the step
+        path = [0]
+        while len(path) < a_want and T_step > 1 and children[path[-1]]:
+            path.append(int(rng.choice(children[path[-1]])))
+        # the forced argmax needs the node tokens, which depend only on state known before the step
+        cand_now = st.cand[0].cpu().numpy()
+        root_now = int(st.root_token[0])
+        tok_now = orc.tree_tokens(root_now, cand_now, pair.parent if T_step > 1 else [-1], pair.rank if T_step > 1 else [0])
+        forced = np.full(T, -1, dtype=np.int64)
+        for j, n in enumerate(path):
+            forced[n] = tok_now[path[j + 1]] if j + 1 < len(path) else (1000 + step) % cfg["vocab"]
+        # a forced token may collide with a sibling's token; the oracle's walk is the arbiter
+        want_path = orc.accept_path(forced[:T_step], tok_now, (pair.parent if T_step > 1 else [-1]))
+        taps.forced_node_argmax.copy_(torch.from_numpy(forced).to(torch.int32).cuda())
+        taps.forced_gate_hidden[0] = torch.from_numpy(hidden).cuda()
+        pair.engine.verify_step(st, 1)
+        torch.cuda.synchronize()
+        a = int(st.accept_len[0])
+        assert taps.node_token[:T_step].cpu().numpy().tolist() == tok_now.tolist(), step
+        assert st.accepted_nodes[0, :a].cpu().tolist() == want_path, (step, want_path)
+        assert st.accepted_tokens[0, :a].cpu().tolist() == [int(tok_now[n]) for n in want_path]
+        assert int(st.root_token[0]) == int(forced[want_path[-1]])
+        L += len(want_path)
+        assert int(st.kv_len[0]) == L
+        assert abs(float(st.entropy[0]) - S_want) < 1e-3 and int(st.gate_flag[0]) == flag_want, step
+        n_ar += T_step == 1
+        n_tree += T_step > 1
+        committed += a
+        flag = flag_want
+    assert int(st.status[0]) == 0 and L <= cap - T
+    say(f"7B schedule: {n_tree} tree steps, {n_ar} AR steps, {committed} tokens committed, final L {L}")
+    assert n_ar > 40 and n_tree > 120
+    pair.engine.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# configs[4]: eight independent 7B-shape sequences, prefixes drawn from 512..4096, per-sequence
+# gate decisions, one launch.  The oracle checks one sampled root-to-leaf path of a tree sequence
+# and the single row of an auto-regressive one.
+# ---------------------------------------------------------------------------------------------
+def test_7b_batch8_mixed_launch(pair_7b):
+    Bn, cap = 8, 4224
+    pair = H.Pair("7b", BF16, "p63", max_batch=Bn, kv_capacity=cap, share=pair_7b)
+    cfg, T, tol = pair.cfg, pair.T, H.TOL_BF16
+    rng = np.random.default_rng(21)
+    Ls = rng.integers(512, 4097, size=Bn)
+    flags = (rng.random(Bn) < 0.3).astype(np.int32)
+    flags[0], flags[1] = 0, 1                       # at least one of each kind
+    st = pair.engine.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, Bn, cap, seed=4, dtype=torch.bfloat16, device="cuda"))
+    roots = synth.make_token_ids(Bn, cfg["vocab"], seed=6)
+    cands = synth.make_candidates(cfg, Bn, seed=7)
+    st.kv_len.copy_(torch.from_numpy(Ls.astype(np.int32)).cuda())
+    st.root_token.copy_(roots.cuda())
+    st.cand.copy_(cands.cuda())
+    st.gate_flag.copy_(torch.from_numpy(flags).cuda())
+    taps = pair.taps()
+    kv_before = {b: st.kv[:, :, b].clone() for b in (0, 1)}
+    pair.engine.verify_step(st, Bn)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    rows = int(np.sum(np.where(flags == 1, 1, T)))
+    say(f"7B batch 8: prefixes {Ls.tolist()}, flags {flags.tolist()}, {rows} packed rows")
+    depth, _ = orc.tree_tables(pair.parent)
+    leaf = max(n for n in range(T) if depth[n] == cfg["n_cerb_heads"])
+    for b in (0, 1):
+        nodes = []
+        n = leaf if flags[b] == 0 else 0
+        while n >= 0:
+            nodes.append(n)
+            n = pair.parent[n]
+        nodes.reverse()
+        chain_parent = [-1] + list(range(len(nodes) - 1))
+        chain_rank = [pair.rank[n] for n in nodes]
+        kvb = kv_before[b]
+        kv_host = [(kvb[l, 0].double().cpu().numpy(), kvb[l, 1].double().cpu().numpy()) for l in range(cfg["n_layers"])]
+        ost = orc.new_state(kv_host, int(Ls[b]), int(roots[b]), cands[b].numpy(), 0)
+        out = orc.verify_step(cfg, pair.W, chain_parent, chain_rank, ost)
+        idx = torch.tensor([b * T + n for n in nodes])
+        assert np.array_equal(taps.node_token[idx].cpu().numpy(), out["tok"])
+        err = float(np.max(np.abs(taps.logits[idx].double().cpu().numpy() - out["logits"])))
+        say(f"7B batch 8 seq {b} (L={Ls[b]}, flag={flags[b]}): logits max-abs err {err:.3e} on nodes {nodes}")
+        assert err <= tol.logits
+        srt = -np.sort(-out["logits"], axis=1)
+        safe = (srt[:, 0] - srt[:, 1]) > 2 * tol.logits
+        assert np.array_equal(taps.node_argmax[idx].cpu().numpy()[safe], np.argmax(out["logits"], axis=1)[safe])
+        # random candidates never match the model's own token: only the root is accepted
+        if safe[0]:
+            assert int(st.accept_len[b]) == 1 == out["accept_len"]
+            assert int(st.kv_len[b]) == Ls[b] + 1 and int(st.root_token[b]) == out["root"]
+            assert abs(float(st.entropy[b]) - out["entropy"]) <= tol.entropy
+    pair.engine.close()
