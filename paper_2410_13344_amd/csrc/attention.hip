@@ -100,43 +100,39 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   const int c = tree ? nprefix : blockIdx.x;      // partial slot
   const int key0 = c * CK;
 
+  // One source description for both kinds of chunk, so the staging below is straight-line code with
+  // every global load (K, V and the wave's q fragments) issued before the first LDS write: a loop of
+  // load-then-store pairs would pay one memory round trip per iteration.
+  const bf16_t *Kb, *Vb;
+  size_t rstride;
+  int nvalid;                                      // rows of this chunk that exist
   if (tree) {
-    const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.ktree) + (size_t)row0 * a.nH * DH + h * DH;
-    const bf16_t* Vt = reinterpret_cast<const bf16_t*>(a.vtree) + (size_t)row0 * a.nH * DH + h * DH;
-    for (int i = threadIdx.x; i < CK * PPR; i += 256) {
-      const int key = i / PPR, pc = i % PPR;
-      const int m = key & 63;                     // tree node
-      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (m < Tb) {
-        const size_t off = (size_t)m * a.nH * DH + (key >= 64 ? a.q_lo_off : 0);
-        kk = reinterpret_cast<const uint4*>(Kt + off)[pc];
-        vv = reinterpret_cast<const uint4*>(Vt + off)[pc];
-      }
-      const int sw = pc ^ (key & (PPR - 1));
-      *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = kk;
-      *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = vv;
-    }
+    Kb = reinterpret_cast<const bf16_t*>(a.ktree) + (size_t)row0 * a.nH * DH + h * DH;
+    Vb = reinterpret_cast<const bf16_t*>(a.vtree) + (size_t)row0 * a.nH * DH + h * DH;
+    rstride = (size_t)a.nH * DH;
+    nvalid = Tb;
   } else {
-    const bf16_t* Kg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap * DH;
-    const bf16_t* Vg = reinterpret_cast<const bf16_t*>(a.kv) + ((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap * DH;
-    for (int i = threadIdx.x; i < CK * PPR; i += 256) {
-      const int key = i / PPR, pc = i % PPR;
-      const int kabs = key0 + key;
-      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (kabs < L) {
-        kk = reinterpret_cast<const uint4*>(Kg + (size_t)kabs * DH)[pc];
-        vv = reinterpret_cast<const uint4*>(Vg + (size_t)kabs * DH)[pc];
-      }
-      const int sw = pc ^ (key & (PPR - 1));
-      *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = kk;
-      *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = vv;
-    }
+    Kb = reinterpret_cast<const bf16_t*>(a.kv) + (((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap + key0) * DH;
+    Vb = reinterpret_cast<const bf16_t*>(a.kv) + (((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap + key0) * DH;
+    rstride = DH;
+    nvalid = min(CK, L - key0);                    // >= 1: the block index is below ceil(L / CK)
   }
-  __syncthreads();
+  const size_t lo_plane = tree ? a.q_lo_off : 0;   // LDS rows 64.. of the tree chunk: lo halves of rows 0..63
+  const int rmask = tree ? 63 : CK - 1;
+  constexpr int NI = CK * PPR / 256;
+  uint4 kk[NI], vv[NI];
+#pragma unroll
+  for (int it = 0; it < NI; ++it) {
+    const int i = it * 256 + threadIdx.x;
+    const int key = i / PPR, pc = i % PPR;
+    const int m = key & rmask;
+    const size_t off = (size_t)min(m, nvalid - 1) * rstride + ((key & ~rmask) ? lo_plane : 0);
+    kk[it] = reinterpret_cast<const uint4*>(Kb + off)[pc];
+    vv[it] = reinterpret_cast<const uint4*>(Vb + off)[pc];
+  }
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lq = lane & 15, g = lane >> 4;
-  if (wave * 16 >= Tb) return;
   const int qnode = wave * 16 + lq;
   const bool qvalid = qnode < Tb;
   const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.q) + (size_t)(row0 + min(qnode, Tb - 1)) * (a.nH * DH) + h * DH;
@@ -146,7 +142,20 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     qf[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + g * 8);
     qfl[ks] = *reinterpret_cast<const uint4*>(qrow + a.q_lo_off + ks * 32 + g * 8);
   }
-  const unsigned long long amask = qvalid ? a.anc[qnode] : 0ull;
+
+  const unsigned long long amask = a.anc[min(qnode, Tb - 1)] & (qvalid ? ~0ull : 0ull);
+
+#pragma unroll
+  for (int it = 0; it < NI; ++it) {
+    const int i = it * 256 + threadIdx.x;
+    const int key = i / PPR, pc = i % PPR;
+    const unsigned ok = (key & rmask) < nvalid ? 0xffffffffu : 0u;   // rows that do not exist are staged as zeros
+    const int sw = pc ^ (key & (PPR - 1));
+    *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = make_uint4(kk[it].x & ok, kk[it].y & ok, kk[it].z & ok, kk[it].w & ok);
+    *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = make_uint4(vv[it].x & ok, vv[it].y & ok, vv[it].z & ok, vv[it].w & ok);
+  }
+  __syncthreads();
+  if (wave * 16 >= Tb) return;
   const float scale = rsqrtf((float)DH);
 
   float s[CK / 16][4];
@@ -246,6 +255,9 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   }
 }
 
+// Merges the chunk partials of one (row, head): out = sum_c w_c o_c / sum_c w_c l_c with
+// w_c = exp(m_c - max m).  Chunks are taken eight at a time, all loads of a batch in flight together,
+// with a running maximum between batches.
 template <int DH>
 __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
   const int r = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
@@ -253,14 +265,32 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
   const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
   const int nch = (a.rm.seq_L[b] + 127) / 128 + 1;   // committed-row chunks + the tree chunk
   const size_t base = (((size_t)b * a.nH + h) * a.n_chunks_max) * 64 + node;
-  float M = -INFINITY;
-  for (int c = 0; c < nch; ++c) M = fmaxf(M, a.part_ml[(base + (size_t)c * 64) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int c = 0; c < nch; ++c) {
-    const size_t slot = base + (size_t)c * 64;
-    const float w = __expf(a.part_ml[slot * 2] - M);
-    den += w * a.part_ml[slot * 2 + 1];
-    num += w * a.part_o[slot * DH + t];
+  constexpr int NB = 8;
+  float M = -INFINITY, num = 0.f, den = 0.f;
+  for (int c0 = 0; c0 < nch; c0 += NB) {
+    float mv[NB], lv[NB], ov[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const size_t slot = base + (size_t)min(c0 + j, nch - 1) * 64;
+      const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + slot * 2);
+      mv[j] = ml.x;
+      lv[j] = ml.y;
+      ov[j] = a.part_o[slot * DH + t];
+    }
+    float Mn = M;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) Mn = fmaxf(Mn, (c0 + j < nch) ? mv[j] : -INFINITY);
+    // every query sees at least itself in the tree chunk, but a batch of fully masked chunks keeps M = -inf
+    const float corr = (M == -INFINITY) ? 0.f : __expf(M - Mn);
+    num *= corr;
+    den *= corr;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const float w = (c0 + j < nch && mv[j] != -INFINITY) ? __expf(mv[j] - Mn) : 0.f;
+      den += w * lv[j];
+      num += w * ov[j];
+    }
+    M = Mn;
   }
   st_a(reinterpret_cast<bf16_t*>(a.out) + (size_t)r * a.nH * DH + h * DH + t, a.out_lo_off, num / den);
 }

@@ -9,7 +9,7 @@
 namespace cerb {
 
 // ---------------------------------------------------------------------------------------------
-// block reductions (blockDim.x a multiple of 64, at most 256)
+// block reductions (blockDim.x a multiple of 64, at most 1024: sh holds one entry per wave)
 // ---------------------------------------------------------------------------------------------
 template <typename V>
 __device__ __forceinline__ V block_sum(V v, V* sh) {
@@ -55,6 +55,43 @@ __device__ __forceinline__ void block_argmax(float& bv, int& bi, float* shv, int
   bv = shv[0]; bi = shi[0];
   for (int w = 1; w < nw; ++w) better(bv, bi, shv[w], shi[w]);
 }
+
+// ---------------------------------------------------------------------------------------------
+// Split-K partials are summed by their consumer, in split order.  All MAXS loads are issued before
+// the first add: a loop with a run-time trip count makes the compiler wait for every load in turn,
+// S memory round trips in a row, which is what these kernels' run time would consist of.  Splits
+// >= S re-read the last valid split (a cache hit) and are dropped by a select.  MAXS == 0: no loads.
+// ---------------------------------------------------------------------------------------------
+template <int MAXS, typename V>
+struct Parts {
+  V v[MAXS > 0 ? MAXS : 1];
+  __device__ __forceinline__ void load(const float* p, size_t pstride, int S) {
+#pragma unroll
+    for (int s = 0; s < MAXS; ++s) v[s] = *reinterpret_cast<const V*>(p + (size_t)min(s, S - 1) * pstride);
+  }
+};
+template <int MAXS>
+__device__ __forceinline__ float add_parts(float a, const Parts<MAXS, float>& P, int S) {
+#pragma unroll
+  for (int s = 0; s < MAXS; ++s) a += (s < S) ? P.v[s] : 0.f;
+  return a;
+}
+template <int MAXS>
+__device__ __forceinline__ float4 add_parts(float4 a, const Parts<MAXS, float4>& P, int S) {
+#pragma unroll
+  for (int s = 0; s < MAXS; ++s) {
+    const bool on = s < S;
+    a.x += on ? P.v[s].x : 0.f; a.y += on ? P.v[s].y : 0.f; a.z += on ? P.v[s].z : 0.f; a.w += on ? P.v[s].w : 0.f;
+  }
+  return a;
+}
+
+// smallest compiled bucket that holds S splits
+#define CERB_S_BUCKET(S, CALL)                                                                     \
+  do {                                                                                             \
+    if ((S) <= 0) { CALL(0); } else if ((S) <= 2) { CALL(2); } else if ((S) <= 4) { CALL(4); }     \
+    else if ((S) <= 8) { CALL(8); } else { CALL(16); }                                             \
+  } while (0)
 
 // ---------------------------------------------------------------------------------------------
 // Tree assembly (Algorithm 1 line 1 and the Candidates tuple of lines 11-12): which rows this step
@@ -123,30 +160,31 @@ hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, floa
 // ---------------------------------------------------------------------------------------------
 // x += sum of the previous GEMM's split-K partials (the residual add), then RMSNorm:
 // out = x * gain / sqrt(mean(x^2) + eps), rounded to the GEMM input type.  d <= 8192, d % 4 == 0.
-// One workgroup of 512 threads per row; a thread owns up to four float4 column groups, loaded once
-// (x and every partial, all loads independent), so the row is read exactly once.
-template <typename T>
-__global__ __launch_bounds__(512) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ part, int S,
-                                                     size_t pstride, const float* __restrict__ gain, float eps,
-                                                     T* __restrict__ out, size_t lo_off, float* __restrict__ out_f32,
-                                                     float* __restrict__ tap, const RowMap rm, int d, int T_tree) {
-  __shared__ float sh[8];
+// One workgroup of 1024 threads per row; a thread owns up to two float4 column groups and has x and
+// every partial of a group in flight together, so the row is read exactly once, in one round trip.
+template <typename T, int MAXS>
+__global__ __launch_bounds__(1024) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ part, int S,
+                                                      size_t pstride, const float* __restrict__ gain, float eps,
+                                                      T* __restrict__ out, size_t lo_off, float* __restrict__ out_f32,
+                                                      float* __restrict__ tap, const RowMap rm, int d, int T_tree) {
+  __shared__ float sh[16];
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   float* xr = x + (size_t)r * d;
-  float4 v[4];
+  float4 v[2], g[2];
   float ss = 0.f;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int c = (it * 512 + threadIdx.x) * 4;
+  for (int it = 0; it < 2; ++it) {
+    const int c = (it * 1024 + threadIdx.x) * 4;
     v[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+    g[it] = v[it];
     if (c < d) {
+      Parts<MAXS, float4> P;
+      P.load(part + (size_t)r * d + c, pstride, S);
       v[it] = *reinterpret_cast<const float4*>(xr + c);
-      for (int s = 0; s < S; ++s) {
-        const float4 p = *reinterpret_cast<const float4*>(part + s * pstride + (size_t)r * d + c);
-        v[it].x += p.x; v[it].y += p.y; v[it].z += p.z; v[it].w += p.w;
-      }
-      if (S > 0) *reinterpret_cast<float4*>(xr + c) = v[it];
+      g[it] = *reinterpret_cast<const float4*>(gain + c);
+      v[it] = add_parts(v[it], P, S);
+      if (MAXS > 0) *reinterpret_cast<float4*>(xr + c) = v[it];
       ss += v[it].x * v[it].x + v[it].y * v[it].y + v[it].z * v[it].z + v[it].w * v[it].w;
     }
   }
@@ -154,11 +192,10 @@ __global__ __launch_bounds__(512) void k_add_rmsnorm(float* __restrict__ x, cons
   const float sc = 1.0f / sqrtf(ss / (float)d + eps);
   float* tp = tap ? tap + ((size_t)rm.row_seq[r] * T_tree + rm.row_node[r]) * d : nullptr;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int c = (it * 512 + threadIdx.x) * 4;
+  for (int it = 0; it < 2; ++it) {
+    const int c = (it * 1024 + threadIdx.x) * 4;
     if (c < d) {
-      const float4 g = *reinterpret_cast<const float4*>(gain + c);
-      const float o[4] = {v[it].x * g.x * sc, v[it].y * g.y * sc, v[it].z * g.z * sc, v[it].w * g.w * sc};
+      const float o[4] = {v[it].x * g[it].x * sc, v[it].y * g[it].y * sc, v[it].z * g[it].z * sc, v[it].w * g[it].w * sc};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         st_a(out + (size_t)r * d + c + e, lo_off, o[e]);
@@ -171,12 +208,15 @@ __global__ __launch_bounds__(512) void k_add_rmsnorm(float* __restrict__ x, cons
 
 hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s) {
-  if (D.dtype == 0)
-    hipLaunchKernelGGL((k_add_rmsnorm<float>), dim3(rows_max), dim3(512), 0, s, x, part, S, pstride, gain, D.eps, (float*)out,
-                       (size_t)0, out_f32, tap, rm, D.d, D.T);
-  else
-    hipLaunchKernelGGL((k_add_rmsnorm<bf16_t>), dim3(rows_max), dim3(512), 0, s, x, part, S, pstride, gain, D.eps,
-                       (bf16_t*)out, (size_t)D.R64 * D.d, out_f32, tap, rm, D.d, D.T);
+#define CERB_CALL(MS)                                                                                                   \
+  if (D.dtype == 0)                                                                                                     \
+    hipLaunchKernelGGL((k_add_rmsnorm<float, MS>), dim3(rows_max), dim3(1024), 0, s, x, part, S, pstride, gain, D.eps,  \
+                       (float*)out, (size_t)0, out_f32, tap, rm, D.d, D.T);                                             \
+  else                                                                                                                  \
+    hipLaunchKernelGGL((k_add_rmsnorm<bf16_t, MS>), dim3(rows_max), dim3(1024), 0, s, x, part, S, pstride, gain, D.eps, \
+                       (bf16_t*)out, (size_t)D.R64 * D.d, out_f32, tap, rm, D.d, D.T)
+  CERB_S_BUCKET(S, CERB_CALL);
+#undef CERB_CALL
   return hipGetLastError();
 }
 
@@ -193,6 +233,8 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
   const int b = rm.row_seq[r], node = rm.row_node[r];
   const int d = D.d, dh = D.dh, half = dh / 2, N = 3 * d;
   const int c0 = h * dh + j, c1 = c0 + half;
+  // (a plain loop: these partials are still in L2 and the kernel is bound by their volume, so having
+  // every split's loads in flight at once gains nothing here)
   float v[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int s = 0; s < S; ++s) {
     const float* p = part + s * pstride + (size_t)r * N;
