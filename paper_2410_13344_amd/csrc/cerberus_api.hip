@@ -233,6 +233,10 @@ void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const
       const int chunks = P.K / 256;
       int S = force_s1 ? 1 : std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
       S = std::min(S, std::min(c->max_split, chunks));
+      // an uneven split leaves some workgroups with less to do and costs a whole extra partial: take
+      // the next lower split that divides the chunks, if there is one nearby
+      for (int s2 = S; s2 * 5 >= S * 3 && s2 >= 1; --s2)
+        if (chunks % s2 == 0) { S = s2; break; }
       const int cps = ceil_div(chunks, S);
       P.S = ceil_div(chunks, cps);
       P.kps = cps * 8;

@@ -38,7 +38,9 @@ __device__ __forceinline__ float block_max(float v, float* sh) {
 
 // best = larger value, ties to the lower index
 __device__ __forceinline__ void better(float& bv, int& bi, float v, int i) {
-  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+  const bool take = v > bv || (v == bv && i < bi);   // selects, not branches: callers run this per element
+  bv = take ? v : bv;
+  bi = take ? i : bi;
 }
 
 __device__ __forceinline__ void block_argmax(float& bv, int& bi, float* shv, int* shi) {
@@ -533,13 +535,19 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
   // every thread keeps its slice of the row in registers: float4 groups tid, tid + 1024, ...
   constexpr int kG = 16;                       // up to 16 * 4096 = 65536 vocabulary entries per pass
   float4 val[kG];
+  // all loads first (clamped, V % 4 == 0), then the entries past the vocabulary become -inf
 #pragma unroll
   for (int k = 0; k < kG; ++k) {
     const int v = (k * 1024 + threadIdx.x) * 4;
-    val[k] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    val[k] = *reinterpret_cast<const float4*>(lg + min(v, V - 4));
+  }
+#pragma unroll
+  for (int k = 0; k < kG; ++k) {
+    const int v = (k * 1024 + threadIdx.x) * 4;
     if (v < V) {
-      val[k] = *reinterpret_cast<const float4*>(lg + v);
       if (tp.head_logits) *reinterpret_cast<float4*>(tp.head_logits + ((size_t)b * Hc + i) * V + v) = val[k];
+    } else {
+      val[k] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
     }
   }
   float pv = INFINITY;
@@ -550,10 +558,13 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
 #pragma unroll
     for (int k = 0; k < kG; ++k) {
       const int v = (k * 1024 + threadIdx.x) * 4;
-      if (val[k].x < pv || (val[k].x == pv && v > pi)) better(bv, bi, val[k].x, v);
-      if (val[k].y < pv || (val[k].y == pv && v + 1 > pi)) better(bv, bi, val[k].y, v + 1);
-      if (val[k].z < pv || (val[k].z == pv && v + 2 > pi)) better(bv, bi, val[k].z, v + 2);
-      if (val[k].w < pv || (val[k].w == pv && v + 3 > pi)) better(bv, bi, val[k].w, v + 3);
+      const float e[4] = {val[k].x, val[k].y, val[k].z, val[k].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        // eligible: strictly after the previous winner in (value descending, id ascending) order
+        const bool el = v < V && (e[j] < pv || (e[j] == pv && v + j > pi));
+        better(bv, bi, el ? e[j] : -INFINITY, el ? v + j : INT_MAX);
+      }
     }
     block_argmax(bv, bi, shv, shi);
     if (bi == INT_MAX) bi = 0;
