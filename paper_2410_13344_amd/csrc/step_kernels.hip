@@ -38,7 +38,7 @@ __device__ __forceinline__ float block_max(float v, float* sh) {
 
 // best = larger value, ties to the lower index
 __device__ __forceinline__ void better(float& bv, int& bi, float v, int i) {
-  const bool take = v > bv || (v == bv && i < bi);   // selects, not branches: callers run this per element
+  const bool take = (v > bv) | ((v == bv) & (i < bi));   // bitwise on purpose: selects, not branches, per element
   bv = take ? v : bv;
   bi = take ? i : bi;
 }
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         // eligible: strictly after the previous winner in (value descending, id ascending) order
-        const bool el = v < V && (e[j] < pv || (e[j] == pv && v + j > pi));
+        const bool el = (v < V) & ((e[j] < pv) | ((e[j] == pv) & (v + j > pi)));
         better(bv, bi, el ? e[j] : -INFINITY, el ? v + j : INT_MAX);
       }
     }
