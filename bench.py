@@ -99,6 +99,9 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--param", action="append", default=[], help="library tuning knob name=value")
+    ap.add_argument("--ar", action="store_true", help="time the plain auto-regressive step (tree of size 1, no heads)")
+    ap.add_argument("--batch", type=int, default=1, help="sequences per launch (prefix lengths spread over [prefix/2, prefix])")
+    ap.add_argument("--mixed", action="store_true", help="with --batch: every third sequence takes the auto-regressive step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling profiler byte counters)")
     args = ap.parse_args()
@@ -126,23 +129,28 @@ def main() -> int:
     L = args.prefix if args.prefix is not None else {"7b": 1024, "13b": 2048, "tiny": 128}[name]
     parent, rank = synth.make_tree(tree_name, cfg["n_cerb_heads"])
     T = len(parent)
-    cap = ((L + T + 127) // 128 + 1) * 128
+    Bn = args.batch
+    assert 1 <= Bn <= 16
+    Ls = [L] if Bn == 1 else [int(round(L / 2 + (L - L / 2) * b / (Bn - 1))) for b in range(Bn)]
+    flags = [1 if (args.ar or (args.mixed and b % 3 == 2)) else 0 for b in range(Bn)]
+    cap = ((max(Ls) + T + 127) // 128 + 1) * 128
     dtype = B.CERBERUS_BF16
     W = synth.make_weights(cfg, seed=0, dtype=torch.bfloat16, device="cuda")
-    eng = B.Engine(cfg, W, parent, rank, dtype, 1, cap)
+    eng = B.Engine(cfg, W, parent, rank, dtype, Bn, cap)
     for kv in args.param:
         k, v = kv.split("=")
         eng.set_param(k, int(v))
     st = eng.new_state()
-    st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
-    st.root_token[0] = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
-    st.cand[0] = synth.make_candidates(cfg, 1, seed=3)[0].cuda()
-    st.gate_flag[0] = 0
-    L_dev = torch.full((1,), L, dtype=torch.int32, device="cuda")
+    st.kv.copy_(synth.make_kv_prefix(cfg, Bn, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
+    st.root_token.copy_(synth.make_token_ids(Bn, cfg["vocab"], seed=2).to(torch.int32).cuda())
+    st.cand.copy_(synth.make_candidates(cfg, Bn, seed=3).cuda())
+    flag_dev = torch.tensor(flags, dtype=torch.int32, device="cuda")
+    L_dev = torch.tensor(Ls, dtype=torch.int32, device="cuda")
 
     def step():
-        st.kv_len.copy_(L_dev)          # every repetition sees the configured prefix length
-        eng.verify_step(st, 1)
+        st.kv_len.copy_(L_dev)          # every repetition sees the configured prefix lengths ...
+        st.gate_flag.copy_(flag_dev)    # ... and step kinds (the threshold is +inf, so the gate itself says parallel)
+        eng.verify_step(st, Bn)
 
     graph = None
     if not args.no_graph:
@@ -175,7 +183,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) / args.steps * 1e3
-    accepted = int(st.accept_len[0]) * args.steps
+    accepted = int(st.accept_len[:Bn].sum()) * args.steps
     assert int(st.status[0]) == 0, "device status word set"
 
     # per-step distribution from events (separate pass)
@@ -194,7 +202,7 @@ def main() -> int:
     tot_bytes = tot_ms = 0.0
     n_launch = 0
     for kind, kname in enumerate(GEMM_KINDS):
-        rows = 1 if kind >= 5 else T
+        rows = 1 if kind >= 5 else sum(1 if f else T for f in flags)
         reps = 3 if kind <= 3 else 20
         B.cerberus_bench_gemm(eng.ctx, kind, rows)
         torch.cuda.synchronize()
@@ -214,12 +222,23 @@ def main() -> int:
             n_launch += launches
     achieved = tot_bytes / tot_ms / 1e6
     alg = algorithmic_bytes(cfg, T, L)
+    if Bn > 1 or args.ar:               # weights once; KV rows and tree rows per sequence; heads only if some sequence runs them
+        per = [algorithmic_bytes(cfg, 1 if f else T, l) for f, l in zip(flags, Ls)]
+        alg = dict(per[0])
+        for k in ("kv_prefix_read", "tree_kv_write_read", "embedding_rows"):
+            alg[k] = sum(q[k] for q in per)
+        if all(flags):
+            alg["heads"] = 0
+        alg["total"] = sum(v for k, v in alg.items() if k != "total")
 
     out = {
         "metric": "verify_step_latency", "value": round(ms_per_step * 1e3, 1), "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{name}-shape bf16, {T}-node tree, KV prefix {L}, batch 1, gate forced parallel",
+        "config": {"workload": (f"{name}-shape bf16, {T}-node tree, KV prefix {L}, batch 1, gate forced parallel"
+                                if Bn == 1 and not args.ar else
+                                f"{name}-shape bf16, batch {Bn}, KV prefixes {Ls}, step kinds (1 = auto-regressive) {flags}, "
+                                f"{T}-node tree"),
                    "graph": graph is not None},
         "latency_us": {"p10": round(float(np.percentile(lat, 10)), 1), "p50": round(float(np.percentile(lat, 50)), 1),
                        "p90": round(float(np.percentile(lat, 90)), 1)},
@@ -229,13 +248,13 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2> (QKV, O, gate/up, down, LM head)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 else None),
+                     "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 and Bn == 1 and not args.ar else None),
                      "traffic_unit": "MB per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, profiles/)",
                      "algorithmic_MB_per_launch": round(tot_bytes / n_launch / 1e6, 1),
                      "avg_launch_us": round(tot_ms * 1e3 / n_launch, 2), "launches_per_step": n_launch,
                      "per_kind": gemm},
     }
-    if not args.no_cpu:
+    if not args.no_cpu and Bn == 1 and not args.ar:
         out["cpu_baseline"] = cpu_baseline(cfg, W, parent, rank, L, cap)
     print(json.dumps(out))
     return 0

@@ -84,6 +84,7 @@ struct GemmBatch {
   int n_skip;
   int nsub;                      // bf16: 16-column slabs per wave (2 or 4); a workgroup covers 64*nsub columns
   int split;                     // bf16: 1 = multiply the hi and the lo activation plane, 0 = hi only
+  int row_blocks;                // bf16: blocks of 64 rows in the launch (set by the launcher)
 };
 
 // launchers (defined next to their kernels)

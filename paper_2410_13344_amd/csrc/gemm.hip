@@ -63,13 +63,21 @@ template <int MT, int NSUB, int SPLIT>
 __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   if (gemm_skip(g)) return;
   const int rows = g.n_rows ? *g.n_rows : g.rows_static;
-  const int m0 = blockIdx.y * (MT * 16);
-  if (m0 >= rows) return;
+  // One-dimensional grid, numbered so that the row blocks of one (column tile, split) have ids 8
+  // apart: consecutive workgroup ids go to the 8 XCDs in turn, so those workgroups land on one XCD
+  // at about the same time and the weight tile comes from HBM once and from that XCD's L2 afterwards.
+  // (Should the hardware map ids differently, only the reuse is lost.)  With one row block the
+  // numbering is the identity.
+  const int RB = g.row_blocks;
+  const int grp = (int)blockIdx.x / (8 * RB), within = (int)blockIdx.x - grp * 8 * RB;
+  const int tile_id = grp * 8 + (within & 7);
+  const int m0 = (within >> 3) * (MT * 16);
+  if (tile_id >= g.tile0[g.n_prob] || m0 >= rows) return;
 
   int pi = 0;
-  while (pi + 1 < g.n_prob && (int)blockIdx.x >= g.tile0[pi + 1]) ++pi;
+  while (pi + 1 < g.n_prob && tile_id >= g.tile0[pi + 1]) ++pi;
   const GemmProb P = g.p[pi];
-  const int local = (int)blockIdx.x - g.tile0[pi];
+  const int local = tile_id - g.tile0[pi];
   const int split = local % P.S;
   const int ntile = local / P.S;
   constexpr int KSC = SPLIT ? 4 : 8;         // k-steps per LDS chunk
@@ -247,18 +255,19 @@ static void launch_bf16(const GemmBatch& g, dim3 grid, hipStream_t s) {
   }
 }
 
-hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t s) {
-  const int wgs = g.tile0[g.n_prob];
+hipError_t launch_gemm(const GemmBatch& plan, int dtype, int rows_max, hipStream_t s) {
+  const int wgs = plan.tile0[plan.n_prob];
   if (wgs <= 0 || rows_max <= 0) return hipSuccess;
   if (dtype == 0) {
-    hipLaunchKernelGGL(k_gemm_f32, dim3(wgs, (rows_max + 15) / 16), dim3(256), 0, s, g);
-  } else if (rows_max <= 16) {
-    launch_bf16<1>(g, dim3(wgs, 1), s);
-  } else if (rows_max <= 32) {
-    launch_bf16<2>(g, dim3(wgs, 1), s);
-  } else {
-    launch_bf16<4>(g, dim3(wgs, (rows_max + 63) / 64), s);
+    hipLaunchKernelGGL(k_gemm_f32, dim3(wgs, (rows_max + 15) / 16), dim3(256), 0, s, plan);
+    return hipGetLastError();
   }
+  GemmBatch g = plan;
+  g.row_blocks = rows_max <= 64 ? 1 : (rows_max + 63) / 64;
+  const dim3 grid((unsigned)((wgs + 7) / 8 * 8 * g.row_blocks));
+  if (rows_max <= 16) launch_bf16<1>(g, grid, s);
+  else if (rows_max <= 32) launch_bf16<2>(g, grid, s);
+  else launch_bf16<4>(g, grid, s);
   return hipGetLastError();
 }
 
