@@ -1,12 +1,16 @@
 """Benchmark of the Cerberus verify step on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b|13b|tiny] [--no-graph] [--no-cpu]
+                    [--ar] [--batch B [--mixed]] [--prefix L] [--tree p63|p120|p150] [--medusa-heads]
+                    [--param name=value]
 
 A step is one full pass of the hot path over one batch: tree assembly, 32 decoder layers over the
 64-node tree with tree-masked attention against a 1024-row KV prefix, LM head and per-node argmax,
 acceptance, KV compaction, entropy gate, Cerberus heads and top-k (gate forced to the parallel path,
 so the heads always run).  Weights, KV prefix and candidates are synthetic (seeded, random-init) and
-resident in HBM before the timed region.  Prints ONE JSON line.
+resident in HBM before the timed region.  Prints ONE JSON line.  The default is the headline
+configuration; --ar (plain auto-regressive step), --batch/--mixed, --workload 13b and --medusa-heads
+time the secondary configurations with the same contract.
 """
 from __future__ import annotations
 
@@ -99,6 +103,9 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--param", action="append", default=[], help="library tuning knob name=value")
+    ap.add_argument("--tree", default=None, help="candidate tree: p63 (default, 64 nodes), p120 or p150 (top-10 per head)")
+    ap.add_argument("--medusa-heads", action="store_true",
+                    help="independent d-wide heads (special_block = -1) instead of the linked Cerberus heads")
     ap.add_argument("--ar", action="store_true", help="time the plain auto-regressive step (tree of size 1, no heads)")
     ap.add_argument("--batch", type=int, default=1, help="sequences per launch (prefix lengths spread over [prefix/2, prefix])")
     ap.add_argument("--mixed", action="store_true", help="with --batch: every third sequence takes the auto-regressive step")
@@ -124,8 +131,11 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     name = args.workload
-    cfg = synth.make_config(name)                      # entropy_threshold = +inf: gate forced parallel
-    tree_name = "tiny" if name == "tiny" else "p63"
+    over = {"special_block": -1} if args.medusa_heads else {}
+    tree_name = args.tree or ("tiny" if name == "tiny" else "p63")
+    if tree_name in ("p120", "p150"):
+        over["topk"] = 10                              # Section 5.1: top-10 predictions per head for the larger trees
+    cfg = synth.make_config(name, **over)              # entropy_threshold = +inf: gate forced parallel
     L = args.prefix if args.prefix is not None else {"7b": 1024, "13b": 2048, "tiny": 128}[name]
     parent, rank = synth.make_tree(tree_name, cfg["n_cerb_heads"])
     T = len(parent)
@@ -236,6 +246,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": (f"{name}-shape bf16, {T}-node tree, KV prefix {L}, batch 1, gate forced parallel"
+                                + (", independent (Medusa-style) heads" if args.medusa_heads else "")
                                 if Bn == 1 and not args.ar else
                                 f"{name}-shape bf16, batch {Bn}, KV prefixes {Ls}, step kinds (1 = auto-regressive) {flags}, "
                                 f"{T}-node tree"),

@@ -53,7 +53,7 @@ enum { CERBERUS_F32 = 0, CERBERUS_BF16 = 1 };
 /* bits of cerberus_state.status (device word) */
 enum { CERBERUS_DEV_KV_OVERFLOW = 1, CERBERUS_DEV_BAD_TOKEN = 2 };
 
-enum { CERBERUS_MAX_TREE = 64, CERBERUS_MAX_HEADS = 8, CERBERUS_MAX_TOPK = 16, CERBERUS_MAX_BATCH = 16 };
+enum { CERBERUS_MAX_TREE = 192, CERBERUS_MAX_HEADS = 8, CERBERUS_MAX_TOPK = 16, CERBERUS_MAX_BATCH = 16 };
 
 /* Model and method parameters (Algorithm 1 "Require": N layers, threshold T; Section 5.1
  * "Training": 4 heads of 4 Resblocks + 1 FC).                                                 */

@@ -1,6 +1,6 @@
 // Tree-masked attention of the verify step.  Row n of a sequence (a tree node) attends to every
 // committed cache row 0..L-1 and to the tree rows L+m whose node m is n itself or an ancestor of n;
-// the ancestor sets are one 64-bit mask per node.  Tree attention is only named in the paper
+// the ancestor sets are bit masks, ceil(T / 64) words per node.  Tree attention is only named in the paper
 // (Sections 1 and 5.1); this is the ancestor-mask reading, with position L + depth(n).
 #include "common.h"
 
@@ -17,7 +17,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
   const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
   const int L = a.rm.seq_L[b], Tb = a.rm.seq_T[b];
   const int dh = a.dh, lane = threadIdx.x;
-  const unsigned long long mask = a.anc[node];
+  const unsigned long long* mask = a.anc + (size_t)node * a.aw;
   const T* q = reinterpret_cast<const T*>(a.q) + (size_t)r * a.nH * dh + h * dh;
   const T* Kb = reinterpret_cast<const T*>(a.kv) + ((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap * dh;
   const T* Vb = reinterpret_cast<const T*>(a.kv) + ((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap * dh;
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
   const T* Kt = reinterpret_cast<const T*>(a.ktree);
   const T* Vt = reinterpret_cast<const T*>(a.vtree);
   for (int p = 0; p < L + Tb; ++p) {
-    if (p >= L && !((mask >> (p - L)) & 1ull)) continue;
+    if (p >= L && !((mask[(p - L) >> 6] >> ((p - L) & 63)) & 1ull)) continue;
     const bool side = Kt != nullptr && p >= L;    // this step's rows at hi + lo precision
     const size_t so = (size_t)(row0 + p - L) * a.nH * dh + h * dh;
     float kv[EPL], vv[EPL];
@@ -88,17 +88,20 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char sK[CK * ROWB];
   __shared__ __attribute__((aligned(16))) unsigned char sV[CK * ROWB];
 
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.y;
+  const int qb_max = a.tc_max;                      // query blocks of 64 tree nodes, as many as tree chunks
+  const int b = blockIdx.z / qb_max, qb = blockIdx.z % qb_max;
   const int L = a.rm.seq_L[b], Tb = a.rm.seq_T[b], row0 = a.rm.seq_row0[b];
-  if (Tb <= 0) return;
-  // The last workgroup of a (head, sequence) takes the tree chunk: the step's own <= 64 rows, read
-  // from the hi + lo side planes (LDS rows 0..63 = hi, 64..127 = lo of the same key).  The others
-  // take 128 committed cache rows each.
-  const bool tree = blockIdx.x == gridDim.x - 1;
+  if (Tb <= 0 || qb * 64 >= Tb) return;
+  // The last tc_max workgroups of a (head, sequence, query block) take the tree chunks: 64 of the
+  // step's own rows each, read from the hi + lo side planes (LDS rows 0..63 = hi, 64..127 = lo of
+  // the same key).  The others take 128 committed cache rows each.
+  const int tci = (int)blockIdx.x - ((int)gridDim.x - a.tc_max);   // >= 0: index of the tree chunk
+  const bool tree = tci >= 0;
   const int nprefix = (L + CK - 1) / CK;
-  if (!tree && (int)blockIdx.x >= nprefix) return;
-  const int c = tree ? nprefix : blockIdx.x;      // partial slot
-  const int key0 = c * CK;
+  if (tree ? tci * 64 >= Tb : (int)blockIdx.x >= nprefix) return;
+  const int c = tree ? nprefix + tci : blockIdx.x;  // partial slot
+  const int key0 = c * CK;                          // first cache row of a prefix chunk
 
   // One source description for both kinds of chunk, so the staging below is straight-line code with
   // every global load (K, V and the wave's q fragments) issued before the first LDS write: a loop of
@@ -107,10 +110,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   size_t rstride;
   int nvalid;                                      // rows of this chunk that exist
   if (tree) {
-    Kb = reinterpret_cast<const bf16_t*>(a.ktree) + (size_t)row0 * a.nH * DH + h * DH;
-    Vb = reinterpret_cast<const bf16_t*>(a.vtree) + (size_t)row0 * a.nH * DH + h * DH;
+    Kb = reinterpret_cast<const bf16_t*>(a.ktree) + (size_t)(row0 + tci * 64) * a.nH * DH + h * DH;
+    Vb = reinterpret_cast<const bf16_t*>(a.vtree) + (size_t)(row0 + tci * 64) * a.nH * DH + h * DH;
     rstride = (size_t)a.nH * DH;
-    nvalid = Tb;
+    nvalid = min(64, Tb - tci * 64);
   } else {
     Kb = reinterpret_cast<const bf16_t*>(a.kv) + (((size_t)(0 * a.Bmax + b) * a.nH + h) * a.cap + key0) * DH;
     Vb = reinterpret_cast<const bf16_t*>(a.kv) + (((size_t)(1 * a.Bmax + b) * a.nH + h) * a.cap + key0) * DH;
@@ -133,7 +136,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lq = lane & 15, g = lane >> 4;
-  const int qnode = wave * 16 + lq;
+  const int qnode = qb * 64 + wave * 16 + lq;
   const bool qvalid = qnode < Tb;
   const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.q) + (size_t)(row0 + min(qnode, Tb - 1)) * (a.nH * DH) + h * DH;
   uint4 qf[KS], qfl[KS];   // hi and lo plane of q
@@ -143,7 +146,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     qfl[ks] = *reinterpret_cast<const uint4*>(qrow + a.q_lo_off + ks * 32 + g * 8);
   }
 
-  const unsigned long long amask = a.anc[min(qnode, Tb - 1)] & (qvalid ? ~0ull : 0ull);
+  const unsigned long long amask = a.anc[(size_t)min(qnode, Tb - 1) * a.aw + max(tci, 0)] & (qvalid ? ~0ull : 0ull);
 
 #pragma unroll
   for (int it = 0; it < NI; ++it) {
@@ -155,7 +158,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = make_uint4(vv[it].x & ok, vv[it].y & ok, vv[it].z & ok, vv[it].w & ok);
   }
   __syncthreads();
-  if (wave * 16 >= Tb) return;
+  if (qb * 64 + wave * 16 >= Tb) return;
   const float scale = rsqrtf((float)DH);
 
   float s[CK / 16][4];
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   }
 
   if (qvalid) {
-    const size_t slot = (((size_t)b * a.nH + h) * a.n_chunks_max + c) * 64 + qnode;
+    const size_t slot = (((size_t)b * a.nH + h) * a.n_chunks_max + c) * a.Tpad + qnode;
     float* po = a.part_o + slot * DH;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -263,15 +266,15 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
   const int r = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
   if (r >= *a.rm.n_rows) return;
   const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
-  const int nch = (a.rm.seq_L[b] + 127) / 128 + 1;   // committed-row chunks + the tree chunk
-  const size_t base = (((size_t)b * a.nH + h) * a.n_chunks_max) * 64 + node;
+  const int nch = (a.rm.seq_L[b] + 127) / 128 + (a.rm.seq_T[b] + 63) / 64;   // committed-row chunks + tree chunks
+  const size_t base = (((size_t)b * a.nH + h) * a.n_chunks_max) * a.Tpad + node;
   constexpr int NB = 8;
   float M = -INFINITY, num = 0.f, den = 0.f;
   for (int c0 = 0; c0 < nch; c0 += NB) {
     float mv[NB], lv[NB], ov[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      const size_t slot = base + (size_t)min(c0 + j, nch - 1) * 64;
+      const size_t slot = base + (size_t)min(c0 + j, nch - 1) * a.Tpad;
       const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + slot * 2);
       mv[j] = ml.x;
       lv[j] = ml.y;
@@ -307,7 +310,7 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, int use_mfma, hipStrea
     }
     return hipGetLastError();
   }
-  dim3 grid(a.n_chunks_max, a.nH, a.batch);   // n_chunks_max = ceil(cap / 128) + 1: the last block is the tree chunk
+  dim3 grid(a.n_chunks_max, a.nH, a.batch * a.tc_max);   // x: ceil(cap / 128) prefix chunks, then tc_max tree chunks; z: (sequence, query block)
   dim3 cgrid(a.rows_max, a.nH);
   if (a.dh == 64) {
     hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(256), 0, s, a);

@@ -136,7 +136,7 @@ void fill_dims(cerberus_ctx* c, const cerberus_config* cfg, const cerberus_tree*
   c->elem = cfg->dtype == CERBERUS_F32 ? 4 : 2;
   c->R64 = (int)align_up((size_t)cfg->max_batch * t->n_nodes, 64);
   D.R64 = c->R64;
-  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128) + 1;  // committed-row chunks + the tree chunk
+  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128) + ceil_div(t->n_nodes, 64);  // committed-row chunks + tree chunks
 }
 
 // Assigns every workspace pointer of the context; with base == nullptr it only measures.
@@ -149,7 +149,8 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->tree.parent = b.take<int>(T);
   c->tree.rank = b.take<int>(T);
   c->tree.depth = b.take<int>(T);
-  c->tree.anc = b.take<unsigned long long>(T);
+  c->tree.aw = ceil_div(T, 64);
+  c->tree.anc = b.take<unsigned long long>((size_t)T * c->tree.aw);
   c->inv_freq = b.take<double>(D.dh / 2);
   c->rm.n_rows = b.take<int>(1);
   c->rm.seq_row0 = b.take<int>(B);
@@ -178,7 +179,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   const size_t nmax = (size_t)std::max(std::max(3 * d, 2 * D.F), D.V);
   c->part_floats = 16 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
   c->part = b.take<float>(c->part_floats);
-  const size_t slots = (size_t)B * D.nH * c->n_chunks_max * 64;
+  const size_t slots = (size_t)B * D.nH * c->n_chunks_max * align_up((size_t)D.T, 64);
   c->attn_po = b.take<float>(slots * D.dh);
   c->attn_ml = b.take<float>(slots * 2);
   for (int i = 0; i < 2; ++i) {
@@ -331,7 +332,7 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
                            rows_max, s));
     AttnArgs aa{};
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
-    aa.anc = c->tree.anc; aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
+    aa.anc = c->tree.anc; aa.aw = c->tree.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
     aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
@@ -425,10 +426,14 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   c->parent.assign(tree->parent, tree->parent + T);
   c->rank.assign(tree->rank, tree->rank + T);
   c->depth.assign(T, 0);
-  c->anc.assign(T, 0ull);
+  const int aw = ceil_div(T, 64);
+  c->anc.assign((size_t)T * aw, 0ull);
   for (int n = 0; n < T; ++n) {
-    if (n > 0) { c->depth[n] = c->depth[c->parent[n]] + 1; c->anc[n] = c->anc[c->parent[n]]; }
-    c->anc[n] |= 1ull << n;
+    if (n > 0) {
+      c->depth[n] = c->depth[c->parent[n]] + 1;
+      for (int w = 0; w < aw; ++w) c->anc[(size_t)n * aw + w] = c->anc[(size_t)c->parent[n] * aw + w];
+    }
+    c->anc[(size_t)n * aw + (n >> 6)] |= 1ull << (n & 63);
   }
   std::vector<double> inv(D.dh / 2);
   for (int j = 0; j < D.dh / 2; ++j) inv[j] = std::pow((double)cfg->rope_theta, -2.0 * j / D.dh);
@@ -445,7 +450,7 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   HIP_INIT(hipMemcpy((void*)c->tree.parent, c->parent.data(), T * sizeof(int), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy((void*)c->tree.rank, c->rank.data(), T * sizeof(int), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy((void*)c->tree.depth, c->depth.data(), T * sizeof(int), hipMemcpyHostToDevice));
-  HIP_INIT(hipMemcpy((void*)c->tree.anc, c->anc.data(), T * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  HIP_INIT(hipMemcpy((void*)c->tree.anc, c->anc.data(), c->anc.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy(c->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice));
 
   hipStream_t s0 = nullptr;

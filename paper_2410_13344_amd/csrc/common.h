@@ -54,7 +54,8 @@ struct TreeDev {
   const int* parent;            // [T]
   const int* rank;              // [T]
   const int* depth;             // [T]
-  const unsigned long long* anc;  // [T] bit m set: node m is the node itself or an ancestor
+  const unsigned long long* anc;  // [T][aw] bit m of the words of node n set: node m is n itself or an ancestor of n
+  int aw;                         // 64-bit words per node, ceil(T / 64)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -100,10 +101,13 @@ struct AttnArgs {
   const void* vtree; //            the tree keys are read from here, the cache only serves rows < L
   void* out;         // [rows][nH*dh] attention output (GEMM A operand; bf16: lo plane out_lo_off elements later)
   size_t out_lo_off;
-  float* part_o;     // [B][nH][n_chunks_max][64][dh]; slot ceil(L/128) of a (seq, head) holds the tree chunk
-  float* part_ml;    // [B][nH][n_chunks_max][64][2]
+  float* part_o;     // [B][nH][n_chunks_max][Tpad][dh]; slots ceil(L/128).. of a (seq, head) hold the tree chunks
+  float* part_ml;    // [B][nH][n_chunks_max][Tpad][2]
   RowMap rm;
-  const unsigned long long* anc;
+  const unsigned long long* anc;   // [T][aw]
+  int aw;            // mask words per node
+  int Tpad;          // tree size rounded up to 64: query rows per partial slot
+  int tc_max;        // tree chunks (64 of this step's rows each) at the end of the chunk grid, ceil(T / 64)
   int batch, Bmax, nH, dh, cap, T;
   int chunk;         // keys per workgroup
   int n_chunks_max;

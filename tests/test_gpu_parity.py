@@ -95,6 +95,32 @@ def test_tiny_steps_match_oracle(tiny_pairs, dtype, attn_mfma, cand_mode):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
+def test_tiny_medusa_heads_mode(tiny_pairs, dtype):
+    """special_block = -1 switches the link between the heads off: every head is a stack of d-wide
+    Resblocks on h_last alone (the Medusa heads the paper compares with, Section 4.1).  Same step,
+    same checks; the heads' candidates and logits must match the oracle's independent heads."""
+    say(f"tiny steps, independent heads, dtype={dtype}")
+    pair = tiny_pairs(dtype, special_block=-1)
+    assert all(w == pair.cfg["d_model"] for ws in synth.head_block_widths(pair.cfg) for w in ws)
+    reps = _run_forced_steps(pair, 4, "heads", 1)
+    assert sum(r.cand_checked for _, r in reps) > 0
+
+
+@pytest.mark.parametrize("tree", ["p120", "p150"])
+@pytest.mark.parametrize("dtype,attn_mfma", [(F32, 0), (BF16, 0), (BF16, 1)])
+def test_tiny_large_trees(dtype, attn_mfma, tree):
+    """Trees of 120 and 150 paths (Section 5.1 "Tree Settings"; 121 / 151 nodes, ranks up to 9):
+    ancestor masks of two and three words, several row blocks, query blocks and tree chunks.  Every
+    node's logits, token and argmax are compared, so every mask word and block is exercised."""
+    say(f"tiny steps, tree {tree}, dtype={dtype} attn_mfma={attn_mfma}")
+    pair = H.Pair("tiny", dtype, tree, seed=0, max_batch=1, kv_capacity=512, topk=10)
+    assert pair.T == int(tree[1:]) + 1
+    reps = _run_forced_steps(pair, 3, "planted", attn_mfma)
+    assert sum(r.argmax_checked for _, r in reps) > 0
+    pair.engine.close()
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
 def test_tiny_gated_steps_take_both_paths(tiny_pairs, dtype):
     """configs[0]: threshold at the median entropy of 64 random states; the gate input of every
     step is one of those states, so auto-regressive and tree steps alternate."""
@@ -280,6 +306,16 @@ def test_7b_full_size_sampled_path_matches_oracle(pair_7b):
     _full_size_sampled_path(pair_7b, 1024, 1280)
 
 
+def test_7b_120_path_tree_sampled_path_matches_oracle(pair_7b):
+    """The tree size of the paper's main table (Section 5.1: 120 paths, top-10 per head): 121 nodes,
+    so two 64-row blocks in every GEMM, two query blocks and two tree chunks in attention, two mask
+    words per node.  The sampled chain ends in the last node, so it crosses both blocks."""
+    pair = H.Pair("7b", BF16, "p120", max_batch=1, kv_capacity=1280, share=pair_7b, topk=10)
+    assert pair.T == 121 and max(pair.rank) < 10
+    _full_size_sampled_path(pair, 1024, 1280)
+    pair.engine.close()
+
+
 def test_13b_full_size_sampled_path_matches_oracle():
     """configs[3]: 40 layers, d 5120, 40 heads, FFN 13824, five decoding heads, prefix 2048."""
     say("13B: building weights and engine")
@@ -291,7 +327,6 @@ def test_13b_full_size_sampled_path_matches_oracle():
 def _full_size_sampled_path(pair, L, cap):
     cfg, T, tol = pair.cfg, pair.T, H.TOL_BF16
     tag = f"{cfg['n_layers']}x{cfg['d_model']}"
-    assert T == 64
     st = pair.engine.new_state()
     st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
     root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
