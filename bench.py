@@ -103,6 +103,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--param", action="append", default=[], help="library tuning knob name=value")
+    ap.add_argument("--decode", type=int, default=0, metavar="N",
+                    help="time N chained steps per call (cerberus_decode: device-side gate, token log); value is per step")
     ap.add_argument("--tree", default=None, help="candidate tree: p63 (default, 64 nodes), p120 or p150 (top-10 per head)")
     ap.add_argument("--medusa-heads", action="store_true",
                     help="independent d-wide heads (special_block = -1) instead of the linked Cerberus heads")
@@ -143,7 +145,7 @@ def main() -> int:
     assert 1 <= Bn <= 16
     Ls = [L] if Bn == 1 else [int(round(L / 2 + (L - L / 2) * b / (Bn - 1))) for b in range(Bn)]
     flags = [1 if (args.ar or (args.mixed and b % 3 == 2)) else 0 for b in range(Bn)]
-    cap = ((max(Ls) + T + 127) // 128 + 1) * 128
+    cap = ((max(Ls) + T + max(args.decode, 1) * (cfg["n_cerb_heads"] + 1) + 127) // 128 + 1) * 128
     dtype = B.CERBERUS_BF16
     W = synth.make_weights(cfg, seed=0, dtype=torch.bfloat16, device="cuda")
     eng = B.Engine(cfg, W, parent, rank, dtype, Bn, cap)
@@ -157,10 +159,18 @@ def main() -> int:
     flag_dev = torch.tensor(flags, dtype=torch.int32, device="cuda")
     L_dev = torch.tensor(Ls, dtype=torch.int32, device="cuda")
 
+    log_tokens = torch.zeros((Bn, max(args.decode, 1) * (cfg["n_cerb_heads"] + 1)), dtype=torch.int32, device="cuda")
+    log_count = torch.zeros(Bn, dtype=torch.int32, device="cuda")
+    per_call = max(args.decode, 1)
+
     def step():
         st.kv_len.copy_(L_dev)          # every repetition sees the configured prefix lengths ...
         st.gate_flag.copy_(flag_dev)    # ... and step kinds (the threshold is +inf, so the gate itself says parallel)
-        eng.verify_step(st, Bn)
+        if args.decode:
+            log_count.zero_()
+            eng.decode(st, Bn, args.decode, log_tokens, log_count)
+        else:
+            eng.verify_step(st, Bn)
 
     graph = None
     if not args.no_graph:
@@ -192,8 +202,8 @@ def main() -> int:
         run()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) / args.steps * 1e3
-    accepted = int(st.accept_len[:Bn].sum()) * args.steps
+    ms_per_step = (t1 - t0) / (args.steps * per_call) * 1e3
+    accepted = (int(log_count.sum()) if args.decode else int(st.accept_len[:Bn].sum())) * args.steps
     assert int(st.status[0]) == 0, "device status word set"
 
     # per-step distribution from events (separate pass)
@@ -204,7 +214,7 @@ def main() -> int:
         run()
         b.record()
     torch.cuda.synchronize()
-    lat = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
+    lat = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3 / per_call
 
     # dominant kernel: the weight-streaming GEMM.  Every kind is replayed back to back over all
     # layers (fresh weights each launch, so no cache reuse) between two events on this stream.
@@ -243,10 +253,11 @@ def main() -> int:
 
     out = {
         "metric": "verify_step_latency", "value": round(ms_per_step * 1e3, 1), "unit": "us",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": args.steps * per_call, "warmup": args.warmup * per_call, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": (f"{name}-shape bf16, {T}-node tree, KV prefix {L}, batch 1, gate forced parallel"
                                 + (", independent (Medusa-style) heads" if args.medusa_heads else "")
+                                + (f", {args.decode} chained steps per call" if args.decode else "")
                                 if Bn == 1 and not args.ar else
                                 f"{name}-shape bf16, batch {Bn}, KV prefixes {Ls}, step kinds (1 = auto-regressive) {flags}, "
                                 f"{T}-node tree"),

@@ -51,7 +51,7 @@ typedef enum {
 enum { CERBERUS_F32 = 0, CERBERUS_BF16 = 1 };
 
 /* bits of cerberus_state.status (device word) */
-enum { CERBERUS_DEV_KV_OVERFLOW = 1, CERBERUS_DEV_BAD_TOKEN = 2 };
+enum { CERBERUS_DEV_KV_OVERFLOW = 1, CERBERUS_DEV_BAD_TOKEN = 2, CERBERUS_DEV_LOG_FULL = 4 };
 
 enum { CERBERUS_MAX_TREE = 192, CERBERUS_MAX_HEADS = 8, CERBERUS_MAX_TOPK = 16, CERBERUS_MAX_BATCH = 16 };
 
@@ -145,6 +145,16 @@ int cerberus_verify_step(cerberus_ctx *ctx, const cerberus_state *st, int32_t ba
 
 /* Same with a tree of size 1 for every sequence, whatever gate_flag says.                      */
 int cerberus_ar_step(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch, void *stream);
+
+/* `n_steps` steps of cerberus_verify_step enqueued back to back (Algorithm 1's loop, lines 6-18):
+ * the gate flag a step leaves on the device selects the shape of the next one, nothing crosses to
+ * the host in between.  After every step the tokens it committed are appended to the log:
+ * out_tokens is DEVICE [batch][out_capacity], out_count DEVICE [batch] (read, then advanced by the
+ * step's accept_len).  A sequence whose log is full keeps decoding, logs nothing more and sets
+ * CERBERUS_DEV_LOG_FULL; a sequence out of cache capacity sits the remaining steps out
+ * (CERBERUS_DEV_KV_OVERFLOW), as in a single step.                                             */
+int cerberus_decode(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch, int32_t n_steps,
+                    int32_t *out_tokens, int32_t out_capacity, int32_t *out_count, void *stream);
 
 /* The gate alone (Section 4.2): for each of `rows` vectors hidden[r][0..d) (DEVICE, fp32),
  * P = softmax(hidden[r]), entropy_out[r] = -sum P log2 P, flag_out[r] = entropy > T.          */

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcerberus.so")
 
 CERBERUS_F32, CERBERUS_BF16 = 0, 1
+CERBERUS_DEV_KV_OVERFLOW, CERBERUS_DEV_BAD_TOKEN, CERBERUS_DEV_LOG_FULL = 1, 2, 4   # bits of the device status word
 DEV_KV_OVERFLOW, DEV_BAD_TOKEN = 1, 2
 
 c_i32p = C.POINTER(C.c_int32)
@@ -71,6 +72,9 @@ def lib() -> C.CDLL:
             f = getattr(L, name)
             f.restype = C.c_int
             f.argtypes = [C.c_void_p, C.POINTER(State), C.c_int32, C.c_void_p]
+        L.cerberus_decode.restype = C.c_int
+        L.cerberus_decode.argtypes = [C.c_void_p, C.POINTER(State), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_void_p]
         L.cerberus_gate.restype = C.c_int
         L.cerberus_gate.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.cerberus_accept.restype = C.c_int
@@ -171,6 +175,12 @@ def cerberus_ar_step(ctx: int, state: State, batch: int, stream=None) -> None:
     _check(lib().cerberus_ar_step(ctx, C.byref(state), batch, _stream_ptr(stream)))
 
 
+def cerberus_decode(ctx: int, state: State, batch: int, n_steps: int, out_tokens: torch.Tensor, out_count: torch.Tensor,
+                    stream=None) -> None:
+    _check(lib().cerberus_decode(ctx, C.byref(state), batch, n_steps, out_tokens.data_ptr(), out_tokens.shape[1],
+                                 out_count.data_ptr(), _stream_ptr(stream)))
+
+
 def cerberus_gate(ctx: int, hidden: torch.Tensor, entropy_out: torch.Tensor, flag_out: torch.Tensor, stream=None) -> None:
     _check(lib().cerberus_gate(ctx, hidden.data_ptr(), hidden.shape[0], entropy_out.data_ptr(), flag_out.data_ptr(),
                                _stream_ptr(stream)))
@@ -266,6 +276,10 @@ class Engine:
 
     def ar_step(self, st: DeviceState, batch: int, stream=None):
         cerberus_ar_step(self.ctx, st.struct, batch, stream)
+
+    def decode(self, st: DeviceState, batch: int, n_steps: int, out_tokens: torch.Tensor, out_count: torch.Tensor,
+               stream=None):
+        cerberus_decode(self.ctx, st.struct, batch, n_steps, out_tokens, out_count, stream)
 
     def set_taps(self, taps: Optional[DeviceTaps]):
         self._taps = taps

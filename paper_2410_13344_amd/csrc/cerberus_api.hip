@@ -514,6 +514,18 @@ int cerberus_ar_step(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch,
   return run_step(ctx, st, batch, stream, ASSEMBLE_FORCE_AR);
 }
 
+int cerberus_decode(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch, int32_t n_steps, int32_t* out_tokens,
+                    int32_t out_capacity, int32_t* out_count, void* stream) {
+  TRY(check_state(ctx, st, batch));
+  if (!out_tokens || !out_count) return fail(CERBERUS_ERR_ARG, "null token log");
+  if (n_steps < 0 || out_capacity < 0) return fail(CERBERUS_ERR_ARG, "negative step count or log capacity");
+  for (int i = 0; i < n_steps; ++i) {
+    TRY(run_step(ctx, st, batch, stream, ASSEMBLE_BY_FLAG));
+    HIP_TRY(launch_log_tokens(ctx->D, *st, batch, out_tokens, out_capacity, out_count, reinterpret_cast<hipStream_t>(stream)));
+  }
+  return CERBERUS_OK;
+}
+
 int cerberus_gate(cerberus_ctx* ctx, const float* hidden, int32_t rows, float* entropy_out, int32_t* flag_out, void* stream) {
   if (!ctx || !hidden || !entropy_out || !flag_out) return fail(CERBERUS_ERR_ARG, "null argument");
   if (rows < 0) return fail(CERBERUS_ERR_ARG, "rows < 0");

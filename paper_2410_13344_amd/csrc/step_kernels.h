@@ -52,6 +52,8 @@ hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const f
                                   int link_next, int batch, hipStream_t s);
 hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& st, const cerberus_taps& tp, int batch,
                        hipStream_t s);
+hipError_t launch_log_tokens(const Dims& D, const cerberus_state& st, int batch, int* out, int cap, int* count,
+                             hipStream_t s);
 hipError_t launch_to_f32(const void* in, float* out, int n, int dtype, hipStream_t s);
 
 }  // namespace cerb

@@ -581,6 +581,29 @@ hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& s
 }
 
 // ---------------------------------------------------------------------------------------------
+// Token log of the multi-step driver: append what the step committed (Algorithm 1 line 16).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_log_tokens(const cerberus_state st, int W, int batch, int* __restrict__ out,
+                                                   int cap, int* __restrict__ count) {
+  const int b = threadIdx.x;
+  if (b >= batch) return;
+  const int a = st.accept_len[b];      // 0 when the sequence sat the step out
+  const int n0 = count[b];
+  int n = n0;
+  for (int j = 0; j < a; ++j) {
+    if (n < cap) out[(size_t)b * cap + n++] = st.accepted_tokens[b * W + j];
+  }
+  if (n - n0 < a) atomicOr(st.status, (int)CERBERUS_DEV_LOG_FULL);
+  count[b] = n;
+}
+
+hipError_t launch_log_tokens(const Dims& D, const cerberus_state& st, int batch, int* out, int cap, int* count,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(k_log_tokens, dim3(1), dim3(64), 0, s, st, D.Hc + 1, batch, out, cap, count);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // init-time helpers
 // ---------------------------------------------------------------------------------------------
 template <typename T>

@@ -55,8 +55,12 @@ def test_workspace_bytes_and_host_validation(L):
     bad_parent[5] = 9                                                  # parent after child
     t2, k2 = B.make_tree(bad_parent, rank)
     assert B.cerberus_workspace_bytes(_cfg(), t2) == 0
-    big, k3 = B.make_tree([-1] + list(range(64)), [0] * 65)
-    assert B.cerberus_workspace_bytes(_cfg(), big) == 0                # more than 64 nodes
+    deep, k3 = B.make_tree([-1] + list(range(64)), [0] * 65)
+    assert B.cerberus_workspace_bytes(_cfg(), deep) == 0               # a chain deeper than the heads
+    # a 4-ary tree in breadth-first order: 192 nodes are the most the library takes
+    for n, ok in ((192, True), (193, False)):
+        t4, k4 = B.make_tree([-1] + [(i - 1) // 4 for i in range(1, n)], [0] + [(i - 1) % 4 for i in range(1, n)])
+        assert (B.cerberus_workspace_bytes(_cfg(), t4) > 0) == ok, n
 
 
 def test_init_rejects_null_arguments_without_a_gpu(L):

@@ -153,6 +153,66 @@ def test_ar_step_entry_point(tiny_pairs, dtype):
         assert out["T"] == 1 and not rep.failures, "; ".join(rep.failures)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_decode_chains_steps_on_the_device_and_logs_tokens(tiny_pairs, dtype):
+    """The multi-step driver: n steps enqueued in one call, the device-side gate flag choosing each
+    next step's shape, committed tokens appended to a device log.  Free-running on both sides (no
+    teacher forcing is possible inside the call), so the comparison stops at the first decision of
+    the oracle whose margin is within the tolerance; the threshold is set between the entropies a
+    dry oracle run produces, so both kinds of step occur."""
+    n_steps = 14
+    tol = H.TOL_F32 if dtype == F32 else H.TOL_BF16_TINY
+    base = tiny_pairs(dtype)
+    dry = _prefilled(base)
+    H.round_oracle_kv(dry, dtype)
+    ent = sorted(base.oracle_step(dry)["entropy"] for _ in range(n_steps))
+    thr = 0.5 * (ent[n_steps // 2 - 1] + ent[n_steps // 2])
+    pair = tiny_pairs(dtype, entropy_threshold=float(thr))
+    pair.engine.set_param("attn_mfma", 1)
+    pair.engine.set_taps(None)
+    ost = _prefilled(pair)
+    H.round_oracle_kv(ost, dtype)
+    st = pair.engine.new_state()
+    H.upload_sequence(st, 0, ost, dtype)
+    L0 = ost["L"]
+    log = torch.full((1, 64), -1, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pair.engine.decode(st, 1, n_steps, log, count)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    got = log[0, :int(count[0])].cpu().tolist()
+    assert int(st.kv_len[0]) == L0 + len(got)
+
+    want, kinds, clear = [], [], True
+    for step in range(n_steps):
+        out = pair.oracle_step(ost)
+        srt = -np.sort(-out["logits"][out["path"]], axis=1)
+        margin = float(np.min(srt[:, 0] - srt[:, 1]))
+        if margin <= 2 * tol.logits or abs(out["entropy"] - thr) <= 2 * tol.entropy:
+            clear = False
+            say(f"  step {step}: oracle margin {margin:.2e}, entropy gap {abs(out['entropy'] - thr):.2e}: comparison ends here")
+            break
+        want += [int(t) for t in out["committed"]]
+        kinds.append(out["T"])
+    say(f"  {len(kinds)} steps compared, tree sizes {kinds}, {len(want)} tokens")
+    assert got[:len(want)] == want
+    assert len(kinds) >= 6 and 1 in kinds and pair.T in kinds        # both kinds of step ran
+    if clear:
+        assert len(got) == len(want) and int(st.gate_flag[0]) == ost["flag"] and int(st.root_token[0]) == ost["root"]
+
+    # a log too short for the tokens: the sequence keeps decoding, the log stops, the status says so
+    st2 = pair.engine.new_state()
+    ost2 = _prefilled(pair)
+    H.round_oracle_kv(ost2, dtype)
+    H.upload_sequence(st2, 0, ost2, dtype)
+    short = torch.full((1, 3), -1, dtype=torch.int32, device="cuda")
+    count2 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pair.engine.decode(st2, 1, 5, short, count2)
+    torch.cuda.synchronize()
+    assert int(count2[0]) == 3 and short[0].cpu().tolist() == got[:3]
+    assert int(st2.status[0]) == B.CERBERUS_DEV_LOG_FULL and int(st2.kv_len[0]) >= L0 + 5
+
+
 def test_gate_entry_point_matches_oracle(tiny_pairs):
     states = synth.make_gate_states(64, 256, seed=0)
     S = np.array([orc.entropy_bits(h) for h in states.numpy()])
