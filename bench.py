@@ -103,6 +103,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--param", action="append", default=[], help="library tuning knob name=value")
+    ap.add_argument("--prefill", type=int, default=0, metavar="N",
+                    help="time the prompt phase (cerberus_prefill) of N tokens from an empty cache; value is per pass of T rows")
     ap.add_argument("--decode", type=int, default=0, metavar="N",
                     help="time N chained steps per call (cerberus_decode: device-side gate, token log); value is per step")
     ap.add_argument("--tree", default=None, help="candidate tree: p63 (default, 64 nodes), p120 or p150 (top-10 per head)")
@@ -146,6 +148,8 @@ def main() -> int:
     Ls = [L] if Bn == 1 else [int(round(L / 2 + (L - L / 2) * b / (Bn - 1))) for b in range(Bn)]
     flags = [1 if (args.ar or (args.mixed and b % 3 == 2)) else 0 for b in range(Bn)]
     cap = ((max(Ls) + T + max(args.decode, 1) * (cfg["n_cerb_heads"] + 1) + 127) // 128 + 1) * 128
+    if args.prefill:
+        cap = ((args.prefill + T + 127) // 128 + 1) * 128
     dtype = B.CERBERUS_BF16
     W = synth.make_weights(cfg, seed=0, dtype=torch.bfloat16, device="cuda")
     eng = B.Engine(cfg, W, parent, rank, dtype, Bn, cap)
@@ -162,11 +166,17 @@ def main() -> int:
     log_tokens = torch.zeros((Bn, max(args.decode, 1) * (cfg["n_cerb_heads"] + 1)), dtype=torch.int32, device="cuda")
     log_count = torch.zeros(Bn, dtype=torch.int32, device="cuda")
     per_call = max(args.decode, 1)
+    if args.prefill:
+        prompt_dev = synth.make_token_ids(args.prefill, cfg["vocab"], seed=4).cuda()
+        per_call = (args.prefill + T - 1) // T          # passes per call
 
     def step():
         st.kv_len.copy_(L_dev)          # every repetition sees the configured prefix lengths ...
         st.gate_flag.copy_(flag_dev)    # ... and step kinds (the threshold is +inf, so the gate itself says parallel)
-        if args.decode:
+        if args.prefill:
+            st.kv_len.zero_()
+            eng.prefill(st, Bn, 0, prompt_dev)
+        elif args.decode:
             log_count.zero_()
             eng.decode(st, Bn, args.decode, log_tokens, log_count)
         else:
@@ -203,7 +213,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) / (args.steps * per_call) * 1e3
-    accepted = (int(log_count.sum()) if args.decode else int(st.accept_len[:Bn].sum())) * args.steps
+    accepted = (args.prefill if args.prefill else int(log_count.sum()) if args.decode else int(st.accept_len[:Bn].sum())) * args.steps
     assert int(st.status[0]) == 0, "device status word set"
 
     # per-step distribution from events (separate pass)
@@ -258,6 +268,8 @@ def main() -> int:
         "config": {"workload": (f"{name}-shape bf16, {T}-node tree, KV prefix {L}, batch 1, gate forced parallel"
                                 + (", independent (Medusa-style) heads" if args.medusa_heads else "")
                                 + (f", {args.decode} chained steps per call" if args.decode else "")
+                                + (f"; prompt phase of {args.prefill} tokens from an empty cache, {per_call} passes per call, "
+                                   "tokens_per_s = prompt tokens" if args.prefill else "")
                                 if Bn == 1 and not args.ar else
                                 f"{name}-shape bf16, batch {Bn}, KV prefixes {Ls}, step kinds (1 = auto-regressive) {flags}, "
                                 f"{T}-node tree"),

@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
             f = getattr(L, name)
             f.restype = C.c_int
             f.argtypes = [C.c_void_p, C.POINTER(State), C.c_int32, C.c_void_p]
+        L.cerberus_prefill.restype = C.c_int
+        L.cerberus_prefill.argtypes = [C.c_void_p, C.POINTER(State), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
         L.cerberus_decode.restype = C.c_int
         L.cerberus_decode.argtypes = [C.c_void_p, C.POINTER(State), C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_void_p]
@@ -175,6 +177,11 @@ def cerberus_ar_step(ctx: int, state: State, batch: int, stream=None) -> None:
     _check(lib().cerberus_ar_step(ctx, C.byref(state), batch, _stream_ptr(stream)))
 
 
+def cerberus_prefill(ctx: int, state: State, batch: int, seq: int, tokens: torch.Tensor, stream=None) -> None:
+    assert tokens.dtype == torch.int32 and tokens.is_cuda and tokens.dim() == 1
+    _check(lib().cerberus_prefill(ctx, C.byref(state), batch, seq, tokens.data_ptr(), tokens.shape[0], _stream_ptr(stream)))
+
+
 def cerberus_decode(ctx: int, state: State, batch: int, n_steps: int, out_tokens: torch.Tensor, out_count: torch.Tensor,
                     stream=None) -> None:
     _check(lib().cerberus_decode(ctx, C.byref(state), batch, n_steps, out_tokens.data_ptr(), out_tokens.shape[1],
@@ -276,6 +283,9 @@ class Engine:
 
     def ar_step(self, st: DeviceState, batch: int, stream=None):
         cerberus_ar_step(self.ctx, st.struct, batch, stream)
+
+    def prefill(self, st: DeviceState, batch: int, seq: int, tokens: torch.Tensor, stream=None):
+        cerberus_prefill(self.ctx, st.struct, batch, seq, tokens, stream)
 
     def decode(self, st: DeviceState, batch: int, n_steps: int, out_tokens: torch.Tensor, out_count: torch.Tensor,
                stream=None):

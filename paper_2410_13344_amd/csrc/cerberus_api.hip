@@ -55,6 +55,7 @@ struct cerberus_ctx {
   int elem = 2;  // bytes per stored element
   std::vector<int> parent, rank, depth;
   std::vector<unsigned long long> anc;
+  TreeDev chain{};   // tables of a chain of T nodes (node i's parent is i-1): the causal mask of a prompt pass
 
   // device memory, all inside the workspace
   TreeDev tree{};
@@ -151,6 +152,12 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->tree.depth = b.take<int>(T);
   c->tree.aw = ceil_div(T, 64);
   c->tree.anc = b.take<unsigned long long>((size_t)T * c->tree.aw);
+  c->chain.T = T;
+  c->chain.parent = c->tree.parent;   // not read in a prompt pass
+  c->chain.rank = c->tree.rank;       // not read in a prompt pass
+  c->chain.depth = b.take<int>(T);
+  c->chain.aw = c->tree.aw;
+  c->chain.anc = b.take<unsigned long long>((size_t)T * c->tree.aw);
   c->inv_freq = b.take<double>(D.dh / 2);
   c->rm.n_rows = b.take<int>(1);
   c->rm.seq_row0 = b.take<int>(B);
@@ -309,15 +316,13 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
     if (rc_ != CERBERUS_OK) return rc_; \
   } while (0)
 
-int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream, int mode) {
-  TRY(check_state(c, st, batch));
-  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+// Embedding, the decoder layers and, with `head`, final norm + LM head + per-row argmax, over the
+// rows the assembly kernel laid out; `tr` supplies the attention mask (candidate tree, or a chain).
+int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_max, const TreeDev& tr, bool head,
+                 hipStream_t s) {
   const Dims& D = c->D;
   const RowMap& rm = c->rm;
-  const int rows_max = (mode == ASSEMBLE_FORCE_AR) ? batch : batch * D.T;
   const size_t kv_layer_bytes = (size_t)2 * D.Bmax * D.nH * D.cap * D.dh * c->elem;
-
-  HIP_TRY(launch_assemble(D, c->tree, rm, *st, c->taps, batch, mode, s));
   HIP_TRY(launch_embed(D, rm, c->embed, c->x, rows_max, s));
 
   const GemmProb* prev = nullptr;  // GEMM whose partials are the pending residual
@@ -332,7 +337,7 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
                            rows_max, s));
     AttnArgs aa{};
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
-    aa.anc = c->tree.anc; aa.aw = c->tree.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
+    aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
     aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
@@ -345,18 +350,20 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
     TRY(run_gemm(c, c->p_down[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
     prev = &c->p_down[l].p[0];
   }
+  if (!head) return CERBERUS_OK;
   HIP_TRY(launch_add_rmsnorm(D, rm, c->x, prev->out, prev->S, (size_t)prev->out_rows * prev->N, c->final_norm, c->xn,
                              c->h_last, c->taps.h_last, rows_max, s));
   TRY(run_gemm(c, c->p_lm, rm.n_rows, 0, rows_max, nullptr, 0, s));
   const GemmProb& pl = c->p_lm.p[0];
   HIP_TRY(launch_row_argmax(D, rm, pl.out, pl.S, (size_t)pl.out_rows * pl.N, c->g, c->taps, rows_max, s));
 
-  HIP_TRY(launch_accept(D, c->tree, rm, c->g, rm.row_tok, *st, c->path, c->last_row, batch, s));
-  if (mode != ASSEMBLE_FORCE_AR) HIP_TRY(launch_compact(D, rm, *st, c->path, batch, s));
-  HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, c->taps.forced_gate_hidden, rm.seq_T, batch, st->entropy,
-                      st->gate_flag, s));
+  return CERBERUS_OK;
+}
 
-  // heads: skipped on the device when every sequence's gate chose the auto-regressive step
+// heads: skipped on the device when every sequence's gate chose the auto-regressive step
+int run_heads(cerberus_ctx* c, const cerberus_state* st, int batch, hipStream_t s) {
+  const Dims& D = c->D;
+  const RowMap& rm = c->rm;
   HIP_TRY(launch_heads_prepare(D, c->h_last, c->last_row, c->hsF[0], c->hsA[0], batch, s));
   for (int st_i = 0; st_i < D.R; ++st_i) {
     TRY(run_gemm(c, c->p_res[st_i], nullptr, batch, batch, st->gate_flag, batch, s));
@@ -374,6 +381,49 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
   ta.seq_T = rm.seq_T;
   for (int i = 0; i < D.Hc; ++i) ta.logits[i] = c->p_fc.p[i].out;
   HIP_TRY(launch_topk(D, ta, *st, c->taps, batch, s));
+  return CERBERUS_OK;
+}
+
+int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream, int mode) {
+  TRY(check_state(c, st, batch));
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  const Dims& D = c->D;
+  const RowMap& rm = c->rm;
+  const int rows_max = (mode == ASSEMBLE_FORCE_AR) ? batch : batch * D.T;
+
+  HIP_TRY(launch_assemble(D, c->tree, rm, *st, c->taps, batch, mode, PromptArgs{}, s));
+  TRY(forward_rows(c, st, batch, rows_max, c->tree, true, s));
+
+  HIP_TRY(launch_accept(D, c->tree, rm, c->g, rm.row_tok, *st, c->path, c->last_row, batch, s));
+  if (mode != ASSEMBLE_FORCE_AR) HIP_TRY(launch_compact(D, rm, *st, c->path, batch, s));
+  HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, c->taps.forced_gate_hidden, rm.seq_T, batch, st->entropy,
+                      st->gate_flag, s));
+  return run_heads(c, st, batch, s);
+}
+
+// Prompt phase for one sequence: passes of up to T rows, each a chain (causal mask, positions
+// L, L+1, ...) whose K/V rows land where they stay.
+int run_prompt(cerberus_ctx* c, const cerberus_state* st, int batch, int seq, const int* tokens, int n_tokens, hipStream_t s) {
+  const Dims& D = c->D;
+  const RowMap& rm = c->rm;
+  // output taps see the prompt rows like any others; values forced for decoding steps do not apply here
+  struct Restore {
+    cerberus_taps& t; cerberus_taps saved;
+    ~Restore() { t = saved; }
+  } restore{c->taps, c->taps};
+  c->taps.forced_node_argmax = nullptr;
+  c->taps.forced_gate_hidden = nullptr;
+  for (int off = 0; off < n_tokens; off += D.T) {
+    const int n = std::min(D.T, n_tokens - off);
+    const bool last = off + n >= n_tokens;
+    HIP_TRY(launch_assemble(D, c->chain, rm, *st, c->taps, batch, ASSEMBLE_PROMPT, PromptArgs{tokens + off, n, seq}, s));
+    TRY(forward_rows(c, st, batch, n, c->chain, last, s));
+    HIP_TRY(launch_prompt_commit(rm, *st, c->g, c->last_row, batch, seq, last ? 1 : 0, s));
+    if (last) {
+      HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, nullptr, rm.seq_T, batch, st->entropy, st->gate_flag, s));
+      TRY(run_heads(c, st, batch, s));
+    }
+  }
   return CERBERUS_OK;
 }
 
@@ -452,6 +502,16 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   HIP_INIT(hipMemcpy((void*)c->tree.depth, c->depth.data(), T * sizeof(int), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy((void*)c->tree.anc, c->anc.data(), c->anc.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy(c->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice));
+  {
+    std::vector<int> cd(T);
+    std::vector<unsigned long long> ca((size_t)T * aw, 0ull);
+    for (int n = 0; n < T; ++n) {
+      cd[n] = n;
+      for (int m = 0; m <= n; ++m) ca[(size_t)n * aw + (m >> 6)] |= 1ull << (m & 63);
+    }
+    HIP_INIT(hipMemcpy((void*)c->chain.depth, cd.data(), T * sizeof(int), hipMemcpyHostToDevice));
+    HIP_INIT(hipMemcpy((void*)c->chain.anc, ca.data(), ca.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
+  }
 
   hipStream_t s0 = nullptr;
   HIP_INIT(launch_to_f32(w->final_norm, c->final_norm, d, D.dtype, s0));
@@ -514,6 +574,14 @@ int cerberus_ar_step(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch,
   return run_step(ctx, st, batch, stream, ASSEMBLE_FORCE_AR);
 }
 
+int cerberus_prefill(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch, int32_t seq, const int32_t* tokens,
+                     int32_t n_tokens, void* stream) {
+  TRY(check_state(ctx, st, batch));
+  if (seq < 0 || seq >= batch) return fail(CERBERUS_ERR_ARG, "sequence index out of 0..batch-1");
+  if (!tokens || n_tokens < 1) return fail(CERBERUS_ERR_ARG, "empty prompt");
+  return run_prompt(ctx, st, batch, seq, tokens, n_tokens, reinterpret_cast<hipStream_t>(stream));
+}
+
 int cerberus_decode(cerberus_ctx* ctx, const cerberus_state* st, int32_t batch, int32_t n_steps, int32_t* out_tokens,
                     int32_t out_capacity, int32_t* out_count, void* stream) {
   TRY(check_state(ctx, st, batch));
@@ -541,7 +609,7 @@ int cerberus_accept(cerberus_ctx* ctx, const int32_t* node_argmax, const int32_t
   if (!node_argmax || !node_token) return fail(CERBERUS_ERR_ARG, "null node arrays");
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   cerberus_taps none{};
-  HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, s));
+  HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, s));
   HIP_TRY(launch_accept(ctx->D, ctx->tree, ctx->rm, node_argmax, node_token, *st, ctx->path, ctx->last_row, batch, s));
   HIP_TRY(launch_compact(ctx->D, ctx->rm, *st, ctx->path, batch, s));
   return CERBERUS_OK;

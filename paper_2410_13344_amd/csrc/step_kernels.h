@@ -11,7 +11,13 @@ struct Dims {
   float eps, threshold;
 };
 
-enum { ASSEMBLE_BY_FLAG = 0, ASSEMBLE_FORCE_AR = 1, ASSEMBLE_FULL_TREE = 2 };
+enum { ASSEMBLE_BY_FLAG = 0, ASSEMBLE_FORCE_AR = 1, ASSEMBLE_FULL_TREE = 2, ASSEMBLE_PROMPT = 3 };
+
+// prompt pass: sequence `seq` runs `n` rows carrying tokens[0..n), every other sequence sits out
+struct PromptArgs {
+  const int* tokens;
+  int n, seq;
+};
 
 struct ResFinishArgs {
   const float* part[CERBERUS_MAX_HEADS];   // GEMM partials of head i: [S][16][width]
@@ -27,7 +33,9 @@ struct TopkArgs {
 };
 
 hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, const cerberus_state& st,
-                           const cerberus_taps& tp, int batch, int mode, hipStream_t s);
+                           const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, hipStream_t s);
+hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, const int* g, int* last_row, int batch, int seq,
+                                int last_pass, hipStream_t s);
 hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, int rows_max, hipStream_t s);
 hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s);

@@ -100,14 +100,15 @@ __device__ __forceinline__ float4 add_parts(float4 a, const Parts<MAXS, float4>&
 // has, and the token / position of each.  One block; sequences pack their rows back to back.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr, const RowMap rm, const cerberus_state st,
-                                                 const cerberus_taps tp, int batch, int mode) {
+                                                 const cerberus_taps tp, int batch, int mode, const PromptArgs pa) {
   __shared__ int sT[CERBERUS_MAX_BATCH], sL[CERBERUS_MAX_BATCH], sRow0[CERBERUS_MAX_BATCH];
   const int t = threadIdx.x;
   if (t < batch) {
     const int L = st.kv_len[t];
     int Tb = tr.T;
     if (mode == ASSEMBLE_FORCE_AR || (mode == ASSEMBLE_BY_FLAG && st.gate_flag[t] != 0)) Tb = 1;
-    if (L < 0 || L + Tb > D.cap) {  // the sequence sits this step out
+    if (mode == ASSEMBLE_PROMPT) Tb = (t == pa.seq) ? pa.n : 0;   // a chain of prompt tokens (tr is the chain's tables)
+    if (Tb > 0 && (L < 0 || L + Tb > D.cap)) {  // the sequence sits this step out
       Tb = 0;
       atomicOr(st.status, (int)CERBERUS_DEV_KV_OVERFLOW);
     }
@@ -130,7 +131,9 @@ __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr,
       rm.row_node[r] = node;
       rm.row_pos[r] = sL[b] + dep;
       if (mode != ASSEMBLE_FULL_TREE) {
-        int tok = node == 0 ? st.root_token[b] : st.cand[(b * D.Hc + dep - 1) * D.topk + tr.rank[node]];
+        int tok;
+        if (mode == ASSEMBLE_PROMPT) tok = pa.tokens[node];
+        else tok = node == 0 ? st.root_token[b] : st.cand[(b * D.Hc + dep - 1) * D.topk + tr.rank[node]];
         if (tok < 0 || tok >= D.V) { atomicOr(st.status, (int)CERBERUS_DEV_BAD_TOKEN); tok = 0; }
         rm.row_tok[r] = tok;
         if (tp.node_token) tp.node_token[b * tr.T + node] = tok;
@@ -140,8 +143,33 @@ __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr,
 }
 
 hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, const cerberus_state& st,
-                           const cerberus_taps& tp, int batch, int mode, hipStream_t s) {
-  hipLaunchKernelGGL(k_assemble, dim3(1), dim3(64), 0, s, D, tr, rm, st, tp, batch, mode);
+                           const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, hipStream_t s) {
+  hipLaunchKernelGGL(k_assemble, dim3(1), dim3(64), 0, s, D, tr, rm, st, tp, batch, mode, pa);
+  return hipGetLastError();
+}
+
+// End of a prompt pass: the rows are where they belong already (row L + i), so committing them is
+// advancing kv_len.  After the last pass the pending token is the base model's choice at the last
+// prompt position, and that row feeds the gate and the heads.
+__global__ void k_prompt_commit(const RowMap rm, const cerberus_state st, const int* __restrict__ g, int* __restrict__ last_row,
+                                int batch, int seq, int last_pass) {
+  const int b = threadIdx.x;
+  if (b >= batch) return;
+  const int n = rm.seq_T[b];              // 0 for every sequence but `seq` (and for `seq` when it did not fit)
+  last_row[b] = -1;
+  if (b != seq || n <= 0) return;
+  st.kv_len[b] = rm.seq_L[b] + n;
+  st.accept_len[b] = 0;
+  if (last_pass) {
+    const int r = rm.seq_row0[b] + n - 1;
+    st.root_token[b] = g[r];
+    last_row[b] = r;
+  }
+}
+
+hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, const int* g, int* last_row, int batch, int seq,
+                                int last_pass, hipStream_t s) {
+  hipLaunchKernelGGL(k_prompt_commit, dim3(1), dim3(64), 0, s, rm, st, g, last_row, batch, seq, last_pass);
   return hipGetLastError();
 }
 

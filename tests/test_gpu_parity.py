@@ -213,6 +213,83 @@ def test_decode_chains_steps_on_the_device_and_logs_tokens(tiny_pairs, dtype):
     assert int(st2.status[0]) == B.CERBERUS_DEV_LOG_FULL and int(st2.kv_len[0]) >= L0 + 5
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_prefill_seeds_the_first_step(tiny_pairs, dtype):
+    """Algorithm 1 lines 1-5: the prompt's causal forward from an empty cache, in passes of T rows
+    (100 tokens = 6 full passes and one of 4), then LM head, gate and heads on the last position.
+    Compared with the oracle's one-shot causal prefill: every K/V row, the logits of the last pass,
+    the pending token, entropy and flag, the candidates; then one decoding step taken from the seeded
+    state on both sides."""
+    n_prompt = 100
+    # bf16: the rows of earlier passes are read back from the bf16 cache while the oracle keeps them
+    # in float64, so the bar is the general bf16 one, not the teacher-forced tiny-shape one
+    tol = H.TOL_F32 if dtype == F32 else H.TOL_BF16
+    pair = tiny_pairs(dtype)
+    cfg, T = pair.cfg, pair.T
+    pair.engine.set_param("attn_mfma", 1)
+    taps = pair.taps()
+    prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=21)
+    st = pair.engine.new_state()
+    st.kv_len[0] = 0
+    st.gate_flag[0] = 1                       # must be overwritten by the gate
+    pair.engine.prefill(st, 1, 0, prompt.cuda())
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0 and int(st.kv_len[0]) == n_prompt and int(st.accept_len[0]) == 0
+
+    # the oracle's prefill, once for the state and once step by step for the intermediate values
+    ost = orc.prefill(cfg, pair.W, prompt.numpy(), capacity=pair.kv_capacity)
+    kv2 = orc.new_kv(cfg, pair.kv_capacity)
+    h_last, logits = orc.decoder_rows(cfg, pair.W, prompt.numpy(), np.arange(n_prompt),
+                                      np.tril(np.ones((n_prompt, n_prompt), dtype=bool)), kv2, 0)
+    for l in range(cfg["n_layers"]):
+        for kvi in (0, 1):
+            got = st.kv[l, kvi, 0, :, :n_prompt].double().cpu().numpy()
+            want = ost["kv"][l][kvi][:, :n_prompt]
+            assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, float(np.max(np.abs(got - want))))
+    n_last = n_prompt % T or T                 # rows of the last pass: taps hold them at slots 0..n_last-1
+    err = float(np.max(np.abs(taps.logits[:n_last].double().cpu().numpy() - logits[-n_last:])))
+    herr = float(np.max(np.abs(taps.h_last[:n_last].double().cpu().numpy() - h_last[-n_last:])))
+    say(f"  prefill: last pass of {n_last} rows, logits err {err:.2e}, h_last err {herr:.2e}")
+    assert err <= tol.logits and herr <= tol.hidden
+    srt = -np.sort(-logits[-1])
+    if srt[0] - srt[1] > 2 * tol.logits:
+        assert int(st.root_token[0]) == ost["root"]
+    S, flag = orc.gate(h_last[-1], cfg["entropy_threshold"])
+    assert abs(float(st.entropy[0]) - S) <= tol.entropy and int(st.gate_flag[0]) == flag == 0
+    want_hl = np.stack(orc.cerberus_heads(cfg, pair.W["heads"], h_last[-1]))
+    hl = taps.head_logits[0].double().cpu().numpy()
+    checked = 0
+    for i in range(cfg["n_cerb_heads"]):
+        tol_i = H.head_logit_tol(tol, want_hl[i])
+        assert float(np.max(np.abs(hl[i] - want_hl[i]))) <= tol_i
+        srt_i = -np.sort(-want_hl[i])[:cfg["topk"] + 1]
+        for j in range(cfg["topk"]):
+            if H._margin_ok(srt_i, j, tol_i):
+                checked += 1
+                assert int(st.cand[0, i, j]) == int(ost["cand"][i, j]), (i, j)
+    assert checked > 0
+
+    # a second sequence's slot is untouched by a prefill of the first: covered by batch = 1 here; the
+    # decoding step that follows runs from the seeded state on both sides
+    if int(st.root_token[0]) == ost["root"] and np.array_equal(st.cand[0].cpu().numpy(), ost["cand"]):
+        out = pair.oracle_step(ost)
+        pair.engine.verify_step(st, 1)
+        torch.cuda.synchronize()
+        rep = H.compare_step(cfg, out, st, taps, 0, T, dtype, ost, tol=tol)
+        say(f"  first step after prefill: logits err {rep.max_logit_err:.2e}, accept {out['accept_len']}")
+        assert not rep.failures, "; ".join(rep.failures)
+
+    # a prompt that does not fit: status bit, nothing committed beyond what fitted
+    st3 = pair.engine.new_state()
+    st3.kv_len[0] = pair.kv_capacity - 20
+    pair.engine.prefill(st3, 1, 0, prompt[:40].cuda())
+    torch.cuda.synchronize()
+    assert int(st3.status[0]) & B.CERBERUS_DEV_KV_OVERFLOW
+    assert int(st3.kv_len[0]) == pair.kv_capacity - 20 + 16      # one pass of 16 fitted, the second did not
+    with pytest.raises(RuntimeError):
+        pair.engine.prefill(st3, 1, 1, prompt.cuda())             # sequence index out of range
+
+
 def test_gate_entry_point_matches_oracle(tiny_pairs):
     states = synth.make_gate_states(64, 256, seed=0)
     S = np.array([orc.entropy_bits(h) for h in states.numpy()])
