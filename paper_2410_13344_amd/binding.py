@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libcerberus.so")
 
 CERBERUS_F32, CERBERUS_BF16 = 0, 1
 CERBERUS_DEV_KV_OVERFLOW, CERBERUS_DEV_BAD_TOKEN, CERBERUS_DEV_LOG_FULL = 1, 2, 4   # bits of the device status word
+CERBERUS_MAX_TREE, CERBERUS_MAX_HEADS, CERBERUS_MAX_TOPK, CERBERUS_MAX_BATCH = 192, 8, 16, 16
 DEV_KV_OVERFLOW, DEV_BAD_TOKEN = 1, 2
 
 c_i32p = C.POINTER(C.c_int32)

@@ -212,7 +212,8 @@ def paths_to_tree(paths: Sequence[Path]) -> Tuple[List[int], List[int]]:
 
 def make_tree(name: str, n_heads: int = 4) -> Tuple[List[int], List[int]]:
     """'tiny' = the fixed 16-node tree; 'p63' = 63 generated paths + root = 64 nodes;
-    'chain<k>' = a single path of k nodes below the root (rank 0 everywhere)."""
+    'chain<k>' = a single path of k nodes below the root (rank 0 everywhere); 'bfs<k>x<n>' = the
+    first n nodes of the k-ary tree in breadth-first order."""
     if name == "tiny":
         return paths_to_tree(TINY_TREE_PATHS)
     if name == "root":
@@ -220,6 +221,13 @@ def make_tree(name: str, n_heads: int = 4) -> Tuple[List[int], List[int]]:
     if name.startswith("chain"):
         k = int(name[5:])
         return paths_to_tree([tuple([0] * i) for i in range(k + 1)])
+    if name.startswith("bfs"):                      # 'bfs<k>x<n>': the first n nodes of the k-ary tree in breadth-first order
+        k, n = (int(v) for v in name[3:].split("x"))
+        paths, level = [()], [()]
+        while len(paths) < n:
+            level = [p + (r,) for p in level for r in range(k)]
+            paths += level
+        return paths_to_tree(paths[:n])
     if name.startswith("p"):
         return paths_to_tree(select_paths(n_heads, int(name[1:])))
     raise KeyError(name)

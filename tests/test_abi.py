@@ -74,3 +74,12 @@ def test_init_rejects_null_arguments_without_a_gpu(L):
     assert L.cerberus_verify_step(None, None, 1, None) == -1
     assert L.cerberus_gate(None, None, 1, None, None, None) == -1
     assert L.cerberus_set_param(None, b"attn_mfma", 1) == -1
+
+
+def test_binding_constants_match_the_header():
+    text = open(os.path.join(ROOT, "include", "cerberus.h")).read()
+    for name in ("CERBERUS_MAX_TREE", "CERBERUS_MAX_HEADS", "CERBERUS_MAX_TOPK", "CERBERUS_MAX_BATCH", "CERBERUS_F32",
+                 "CERBERUS_BF16", "CERBERUS_DEV_KV_OVERFLOW", "CERBERUS_DEV_BAD_TOKEN", "CERBERUS_DEV_LOG_FULL"):
+        m = re.search(r"\b" + name + r"\s*=\s*(-?\d+)", text)
+        assert m, name
+        assert getattr(B, name) == int(m.group(1)), name

@@ -427,6 +427,36 @@ def test_tiny_batch_mixed_ar_and_tree_in_one_launch(dtype):
         assert out["T"] == 1 and not rep.failures, f"ar seq {b}: " + "; ".join(rep.failures)
 
 
+def test_tiny_maximum_batch_and_tree():
+    """The largest launch the library takes: 16 sequences, a 192-node tree (three mask words, three
+    query blocks and tree chunks), 13 of them running the whole tree and 3 a single row: 2499 packed
+    rows, 40 row blocks in every GEMM.  Every row of every sequence is compared."""
+    pair = H.Pair("tiny", BF16, "bfs4x192", seed=0, max_batch=16, kv_capacity=384)
+    cfg = pair.cfg
+    assert pair.T == B.CERBERUS_MAX_TREE and pair.max_batch == B.CERBERUS_MAX_BATCH
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    osts = []
+    for b in range(16):
+        prompt = synth.make_token_ids(8 + 11 * b, cfg["vocab"], seed=40 + b).numpy()     # prefixes 8 .. 173
+        ost = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+        ost["flag"] = 1 if b in (3, 8, 15) else 0
+        H.round_oracle_kv(ost, BF16)
+        H.upload_sequence(st, b, ost, BF16)
+        osts.append(ost)
+    outs = [pair.oracle_step(ost) for ost in osts]
+    pair.engine.verify_step(st, 16)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    worst = 0.0
+    for b, (ost, out) in enumerate(zip(osts, outs)):
+        rep = H.compare_step(cfg, out, st, taps, b, pair.T, BF16, ost, tol=H.TOL_BF16_TINY)
+        worst = max(worst, rep.max_logit_err)
+        assert not rep.failures, f"seq {b}: " + "; ".join(rep.failures)
+    say(f"  16 sequences, {sum(o['T'] for o in outs)} rows: worst logits err {worst:.2e}")
+    pair.engine.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # full size: the 7B shape in the launch configuration bench.py times (bf16, 64-node tree, prefix
 # 1024).  The oracle cannot afford all 64 nodes, so it runs one sampled root-to-leaf path as a chain
