@@ -548,9 +548,11 @@ hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const f
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per-head top-k (the heads' token candidates): k rounds of a block-wide argmax, each round
-// restricted to entries that come strictly after the previous winner in the order
-// (value descending, id ascending).  Sequences whose gate chose the auto-regressive step keep
+// Per-head top-k (the heads' token candidates), in the order (value descending, id ascending).
+// Every thread keeps its slice of the row in registers and caches the best entry of its slice that
+// has not been taken yet; a round is one block-wide argmax over those cached entries, after which
+// only the winner's owner rescans its slice for its next best (everyone else's cached entry still
+// comes after the winner in the order).  Sequences whose gate chose the auto-regressive step keep
 // their old candidates.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
@@ -560,8 +562,8 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
   const int i = blockIdx.x, b = blockIdx.y;
   if (st.gate_flag[b] != 0 || a.seq_T[b] <= 0) return;
   const float* lg = a.logits[i] + (size_t)b * V;
-  // every thread keeps its slice of the row in registers: float4 groups tid, tid + 1024, ...
-  constexpr int kG = 16;                       // up to 16 * 4096 = 65536 vocabulary entries per pass
+  // float4 groups tid, tid + 1024, ...: up to 16 * 4096 = 65536 vocabulary entries
+  constexpr int kG = 16;
   float4 val[kG];
   // all loads first (clamped, V % 4 == 0), then the entries past the vocabulary become -inf
 #pragma unroll
@@ -578,27 +580,30 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
       val[k] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
     }
   }
-  float pv = INFINITY;
-  int pi = -1;
-  for (int r = 0; r < topk; ++r) {
-    float bv = -INFINITY;
-    int bi = INT_MAX;
+  // best entry of this thread's slice strictly after (pv, pi) in the order; (-inf, INT_MAX) if none
+  auto scan = [&](float pv, int pi, float& lv, int& li) {
+    lv = -INFINITY;
+    li = INT_MAX;
 #pragma unroll
     for (int k = 0; k < kG; ++k) {
       const int v = (k * 1024 + threadIdx.x) * 4;
       const float e[4] = {val[k].x, val[k].y, val[k].z, val[k].w};
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        // eligible: strictly after the previous winner in (value descending, id ascending) order
         const bool el = (v < V) & ((e[j] < pv) | ((e[j] == pv) & (v + j > pi)));
-        better(bv, bi, el ? e[j] : -INFINITY, el ? v + j : INT_MAX);
+        better(lv, li, el ? e[j] : -INFINITY, el ? v + j : INT_MAX);
       }
     }
+  };
+  float lv;
+  int li;
+  scan(INFINITY, -1, lv, li);
+  for (int r = 0; r < topk; ++r) {
+    float bv = lv;
+    int bi = li;
     block_argmax(bv, bi, shv, shi);
-    if (bi == INT_MAX) bi = 0;
-    if (threadIdx.x == 0) st.cand[((size_t)b * Hc + i) * topk + r] = bi;
-    pv = bv;
-    pi = bi;
+    if (threadIdx.x == 0) st.cand[((size_t)b * Hc + i) * topk + r] = bi == INT_MAX ? 0 : bi;
+    if (li == bi && bi != INT_MAX) scan(bv, bi, lv, li);   // ids are unique: this thread owned the winner
   }
 }
 
