@@ -185,6 +185,29 @@ def test_decoder_causal_forward_matches_torch_library():
     assert np.allclose(lg, lg_t, atol=1e-9)
 
 
+def test_prompt_in_passes_equals_one_shot_prefill():
+    """The prompt phase may be run in passes of a few rows, each a chain appended to the cache
+    (that is how the device library runs it): the cache, the last position's hidden state and
+    logits, and therefore root, gate flag and candidates are those of the one-shot causal forward."""
+    cfg, W = tiny()
+    n, cap = 37, 64
+    toks = synth.make_token_ids(n, cfg["vocab"], seed=9).numpy()
+    ref = orc.prefill(cfg, W, toks, capacity=cap)
+    kv = orc.new_kv(cfg, cap)
+    L = 0
+    for size in (16, 16, 5):                      # passes of the tiny tree's 16 rows, then the rest
+        chain_vis = np.tril(np.ones((size, size), dtype=bool))
+        h, lg = orc.decoder_rows(cfg, W, toks[L:L + size], L + np.arange(size), chain_vis, kv, L)
+        L += size
+    for (K, V), (Kr, Vr) in zip(kv, ref["kv"]):
+        assert np.allclose(K[:, :n], Kr[:, :n], atol=1e-12) and np.allclose(V[:, :n], Vr[:, :n], atol=1e-12)
+    assert int(orc.argmax_lowest(lg[-1])) == ref["root"]
+    S, flag = orc.gate(h[-1], cfg["entropy_threshold"])
+    assert flag == ref["flag"] == 0
+    cand = np.stack([orc.topk_ids(hl, cfg["topk"]) for hl in orc.cerberus_heads(cfg, W["heads"], h[-1])])
+    assert np.array_equal(cand, ref["cand"])
+
+
 # ---------------------------------------------------------------------------------------
 # tree verification: brute force over every root-to-leaf path
 # ---------------------------------------------------------------------------------------
