@@ -290,6 +290,43 @@ def test_prefill_seeds_the_first_step(tiny_pairs, dtype):
         pair.engine.prefill(st3, 1, 1, prompt.cuda())             # sequence index out of range
 
 
+def test_prefill_of_one_sequence_leaves_the_others_alone():
+    """Batch of four: sequences 0, 1 and 3 hold decoding states, sequence 2 gets its prompt.  Nothing
+    of the others may change, and the next launch decodes all four against the oracle."""
+    dtype = F32
+    pair = H.Pair("tiny", dtype, "tiny", seed=0, max_batch=4, kv_capacity=256)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    osts = {}
+    for b, n_prompt in ((0, 33), (1, 90), (3, 17)):
+        prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=60 + b).numpy()
+        osts[b] = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+        H.upload_sequence(st, b, osts[b], dtype)
+    st.kv_len[2] = 0
+    before = {k: getattr(st, k).clone() for k in ("kv", "kv_len", "root_token", "cand", "gate_flag", "entropy", "accept_len")}
+    prompt2 = synth.make_token_ids(45, cfg["vocab"], seed=62)
+    pair.engine.prefill(st, 4, 2, prompt2.cuda())
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0 and int(st.kv_len[2]) == 45
+    others = [0, 1, 3]
+    for k, v in before.items():
+        got = getattr(st, k)
+        if k == "kv":
+            assert torch.equal(got[:, :, others], v[:, :, others])
+        else:
+            assert torch.equal(got[others], v[others]), k
+    osts[2] = orc.prefill(cfg, pair.W, prompt2.numpy(), capacity=pair.kv_capacity)
+    assert int(st.root_token[2]) == osts[2]["root"] and np.array_equal(st.cand[2].cpu().numpy(), osts[2]["cand"])
+    outs = {b: pair.oracle_step(osts[b]) for b in range(4)}
+    pair.engine.verify_step(st, 4)
+    torch.cuda.synchronize()
+    for b in range(4):
+        rep = H.compare_step(cfg, outs[b], st, taps, b, pair.T, dtype, osts[b])
+        assert not rep.failures, f"seq {b}: " + "; ".join(rep.failures)
+    pair.engine.close()
+
+
 def test_gate_entry_point_matches_oracle(tiny_pairs):
     states = synth.make_gate_states(64, 256, seed=0)
     S = np.array([orc.entropy_bits(h) for h in states.numpy()])
