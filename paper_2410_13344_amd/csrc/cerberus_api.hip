@@ -62,7 +62,7 @@ struct cerberus_ctx {
   RowMap rm{};
   double* inv_freq = nullptr;
   int *last_row = nullptr, *path = nullptr, *g = nullptr;
-  float *x = nullptr, *h_last = nullptr, *part = nullptr, *attn_po = nullptr, *attn_ml = nullptr;
+  float *x = nullptr, *h_last = nullptr, *part = nullptr, *attn_po = nullptr, *attn_ml = nullptr, *ssq = nullptr;
   void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr, *ktree = nullptr, *vtree = nullptr;
   void* hsA[2] = {nullptr, nullptr};
   float* hsF[2] = {nullptr, nullptr};
@@ -172,6 +172,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->g = b.take<int>(Rmax);
   c->x = b.take<float>((size_t)R64 * d);
   c->h_last = b.take<float>((size_t)R64 * d);
+  c->ssq = b.take<float>((size_t)R64 * add_gain_blocks(d));
   const int planes = cfg.dtype == CERBERUS_BF16 ? 2 : 1;  // GEMM inputs: hi and lo plane in bf16 mode
   c->xn = b.take<unsigned char>((size_t)planes * R64 * d * el);
   c->q = b.take<unsigned char>((size_t)planes * R64 * d * el);
@@ -327,14 +328,13 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
 
   const GemmProb* prev = nullptr;  // GEMM whose partials are the pending residual
   for (int l = 0; l < D.n_layers; ++l) {
-    HIP_TRY(launch_add_rmsnorm(D, rm, c->x, prev ? prev->out : nullptr, prev ? prev->S : 0,
-                               prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, nullptr, nullptr,
-                               rows_max, s));
+    HIP_TRY(launch_add_gain(D, rm, c->x, prev ? prev->out : nullptr, prev ? prev->S : 0,
+                            prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, c->ssq, rows_max, s));
     TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
     const GemmProb& pq = c->p_qkv[l].p[0];
     void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
     HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, c->ktree, c->vtree,
-                           rows_max, s));
+                           c->ssq, rows_max, s));
     AttnArgs aa{};
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
     aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
@@ -342,11 +342,10 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
     const GemmProb& po = c->p_o[l].p[0];
-    HIP_TRY(launch_add_rmsnorm(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, nullptr,
-                               nullptr, rows_max, s));
+    HIP_TRY(launch_add_gain(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, c->ssq, rows_max, s));
     TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
     const GemmProb& pg = c->p_gu[l].p[0];
-    HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, rows_max, s));
+    HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, c->ssq, rows_max, s));
     TRY(run_gemm(c, c->p_down[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
     prev = &c->p_down[l].p[0];
   }

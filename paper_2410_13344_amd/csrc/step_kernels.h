@@ -39,11 +39,15 @@ hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, cons
 hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, int rows_max, hipStream_t s);
 hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s);
+// residual add + x * gain + per-block sums of x^2 (the RMSNorm scalar is applied by the consumer of the next GEMM)
+int add_gain_blocks(int d);   // sums per row
+hipError_t launch_add_gain(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
+                           const float* gain, void* out, float* ssq, int rows_max, hipStream_t s);
 hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
-                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, int rows_max,
-                          hipStream_t s);
+                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, const float* ssq,
+                          int rows_max, hipStream_t s);
 hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
-                         int rows_max, hipStream_t s);
+                         const float* ssq, int rows_max, hipStream_t s);
 hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, int* g,
                              const cerberus_taps& tp, int rows_max, hipStream_t s);
 hipError_t launch_accept(const Dims& D, const TreeDev& tr, const RowMap& rm, const int* g, const int* tok,

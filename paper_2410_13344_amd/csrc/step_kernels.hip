@@ -251,15 +251,74 @@ hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const f
 }
 
 // ---------------------------------------------------------------------------------------------
+// The per-layer norms, split so that more than one workgroup can work on a row.  RMSNorm is a
+// per-row scalar times x * gain, and a GEMM is linear in its input rows, so the scalar can be applied
+// to the GEMM's output instead: this kernel does the residual add and writes x * gain as the GEMM
+// input plus, per (row, 1024-column block), the block's sum of x^2; the kernel that sums the GEMM's
+// split-K partials (k_rope_kv, k_swiglu) forms 1 / sqrt(mean x^2 + eps) from those sums and scales.
+// Four workgroups per row at d = 4096 instead of one.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int MAXS>
+__global__ __launch_bounds__(256) void k_add_gain(float* __restrict__ x, const float* __restrict__ part, int S, size_t pstride,
+                                                  const float* __restrict__ gain, T* __restrict__ out, size_t lo_off,
+                                                  float* __restrict__ ssq, const RowMap rm, int d) {
+  __shared__ float sh[4];
+  const int r = blockIdx.x, nb = gridDim.y;
+  if (r >= *rm.n_rows) return;
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+  float ss = 0.f;
+  if (c < d) {
+    float* xr = x + (size_t)r * d + c;
+    Parts<MAXS, float4> P;
+    P.load(part + (size_t)r * d + c, pstride, S);
+    float4 v = *reinterpret_cast<const float4*>(xr);
+    const float4 g = *reinterpret_cast<const float4*>(gain + c);
+    v = add_parts(v, P, S);
+    if (MAXS > 0) *reinterpret_cast<float4*>(xr) = v;
+    ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    const float o[4] = {v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) st_a(out + (size_t)r * d + c + e, lo_off, o[e]);
+  }
+  ss = block_sum(ss, sh);
+  if (threadIdx.x == 0) ssq[(size_t)r * nb + blockIdx.y] = ss;
+}
+
+int add_gain_blocks(int d) { return (d + 1023) / 1024; }
+
+hipError_t launch_add_gain(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
+                           const float* gain, void* out, float* ssq, int rows_max, hipStream_t s) {
+  const dim3 grid(rows_max, add_gain_blocks(D.d));
+#define CERB_CALL(MS)                                                                                                  \
+  if (D.dtype == 0)                                                                                                    \
+    hipLaunchKernelGGL((k_add_gain<float, MS>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (float*)out,         \
+                       (size_t)0, ssq, rm, D.d);                                                                       \
+  else                                                                                                                 \
+    hipLaunchKernelGGL((k_add_gain<bf16_t, MS>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (bf16_t*)out,       \
+                       (size_t)D.R64 * D.d, ssq, rm, D.d)
+  CERB_S_BUCKET(S, CERB_CALL);
+#undef CERB_CALL
+  return hipGetLastError();
+}
+
+// 1 / sqrt(mean x^2 + eps) of row r from the block sums k_add_gain left (summed in block order)
+__device__ __forceinline__ float row_rms_scale(const float* __restrict__ ssq, int r, int nb, int d, float eps) {
+  float ss = 0.f;
+  for (int i = 0; i < nb; ++i) ss += ssq[(size_t)r * nb + i];
+  return 1.0f / sqrtf(ss / (float)d + eps);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Sum the QKV partials, rotate q and k (pair (j, j + dh/2) by pos * theta^(-2j/dh)), write q for the
 // attention kernel and k, v into the cache at row L + node.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const double* __restrict__ inv_freq,
                           const RowMap rm, T* __restrict__ q, size_t q_lo_off, T* __restrict__ kv_layer,
-                          T* __restrict__ ktree, T* __restrict__ vtree, const Dims D) {
+                          T* __restrict__ ktree, T* __restrict__ vtree, const float* __restrict__ ssq, int nb, const Dims D) {
   const int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
   if (r >= *rm.n_rows) return;
+  const float rs = row_rms_scale(ssq, r, nb, D.d, D.eps);   // the layer input's RMSNorm scalar, applied to the GEMM output
   const int b = rm.row_seq[r], node = rm.row_node[r];
   const int d = D.d, dh = D.dh, half = dh / 2, N = 3 * d;
   const int c0 = h * dh + j, c1 = c0 + half;
@@ -270,6 +329,8 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
     const float* p = part + s * pstride + (size_t)r * N;
     v[0] += p[c0]; v[1] += p[c1]; v[2] += p[d + c0]; v[3] += p[d + c1]; v[4] += p[2 * d + c0]; v[5] += p[2 * d + c1];
   }
+#pragma unroll
+  for (int e = 0; e < 6; ++e) v[e] *= rs;
   // the angle in double: at position ~4000 an fp32 product is already off by 1e-4 rad
   double snd, csd;
   sincos((double)rm.row_pos[r] * inv_freq[j], &snd, &csd);
@@ -296,40 +357,46 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
 }
 
 hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
-                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, int rows_max,
-                          hipStream_t s) {
+                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, const float* ssq,
+                          int rows_max, hipStream_t s) {
+  const int nb = add_gain_blocks(D.d);
   dim3 grid(rows_max, D.nH), block(D.dh / 2);
   if (D.dtype == 0)
     hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (size_t)0,
-                       (float*)kv_layer, (float*)nullptr, (float*)nullptr, D);
+                       (float*)kv_layer, (float*)nullptr, (float*)nullptr, ssq, nb, D);
   else
     hipLaunchKernelGGL((k_rope_kv<bf16_t>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (bf16_t*)q,
-                       (size_t)D.R64 * D.d, (bf16_t*)kv_layer, (bf16_t*)ktree, (bf16_t*)vtree, D);
+                       (size_t)D.R64 * D.d, (bf16_t*)kv_layer, (bf16_t*)ktree, (bf16_t*)vtree, ssq, nb, D);
   return hipGetLastError();
 }
 
 // act = SiLU(gate) * up from the gate/up partials ([.., 2F]: gate columns first)
 template <typename T>
 __global__ __launch_bounds__(256) void k_swiglu(const float* __restrict__ part, int S, size_t pstride, T* __restrict__ act,
-                                                size_t lo_off, const RowMap rm, int F, int Fpad) {
+                                                size_t lo_off, const RowMap rm, int F, int Fpad,
+                                                const float* __restrict__ ssq, int nb, int d, float eps) {
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   const int f = blockIdx.y * 256 + threadIdx.x;
   if (f >= F) return;
+  const float rs = row_rms_scale(ssq, r, nb, d, eps);   // the FFN input's RMSNorm scalar
   float g = 0.f, u = 0.f;
   for (int s = 0; s < S; ++s) {
     const float* p = part + s * pstride + (size_t)r * 2 * F;
     g += p[f];
     u += p[F + f];
   }
+  g *= rs;
+  u *= rs;
   st_a(act + (size_t)r * Fpad + f, lo_off, g / (1.0f + expf(-g)) * u);
 }
 
 hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
-                         int rows_max, hipStream_t s) {
+                         const float* ssq, int rows_max, hipStream_t s) {
   dim3 grid(rows_max, (D.F + 255) / 256);
-  if (D.dtype == 0) hipLaunchKernelGGL((k_swiglu<float>), grid, dim3(256), 0, s, part, S, pstride, (float*)act, (size_t)0, rm, D.F, D.Fpad);
-  else hipLaunchKernelGGL((k_swiglu<bf16_t>), grid, dim3(256), 0, s, part, S, pstride, (bf16_t*)act, (size_t)D.R64 * D.Fpad, rm, D.F, D.Fpad);
+  const int nb = add_gain_blocks(D.d);
+  if (D.dtype == 0) hipLaunchKernelGGL((k_swiglu<float>), grid, dim3(256), 0, s, part, S, pstride, (float*)act, (size_t)0, rm, D.F, D.Fpad, ssq, nb, D.d, D.eps);
+  else hipLaunchKernelGGL((k_swiglu<bf16_t>), grid, dim3(256), 0, s, part, S, pstride, (bf16_t*)act, (size_t)D.R64 * D.Fpad, rm, D.F, D.Fpad, ssq, nb, D.d, D.eps);
   return hipGetLastError();
 }
 
