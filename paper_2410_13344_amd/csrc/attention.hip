@@ -6,6 +6,9 @@
 
 namespace cerb {
 
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short4v __attribute__((address_space(3))) lds_short4v;
+
 // ---------------------------------------------------------------------------------------------
 // Plain kernel, any element type: one wave per (row, head), lanes over the head dimension, online
 // softmax over the visible keys.  Used in fp32 reference mode and as a cross-check of the MFMA one.
@@ -74,8 +77,8 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
 //   S^T = K Q^T      A = K rows (keys), B = Q (queries)  -> lane: query lane%16, keys 4*(lane/16)+v
 //   softmax stats per query: lane-local over its keys, then across the 4 lane groups
 //   O^T = V^T P^T    B = P^T taken straight from the S^T accumulators: contraction slot (g, e) of a
-//                    32-key block is key 4g+e (e<4) or 16+4g+e-4 (e>=4); A = V^T gathered from LDS
-//                    in the same slot order.
+//                    32-key block is key 4g+e (e<4) or 16+4g+e-4 (e>=4); A = V^T taken from the
+//                    row-major LDS tile with transposing reads, in the same slot order.
 // Writes unnormalised partial outputs with (max, sum) per query; k_attn_combine merges the chunks.
 // ---------------------------------------------------------------------------------------------
 template <int DH>
@@ -228,16 +231,20 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
       pb.u[4 + e] = f32_to_bf16(s[2 * kp + 1][e]);
       pl.u[4 + e] = f32_to_bf16(s[2 * kp + 1][e] - bf16_to_f32(pb.u[4 + e]));
     }
+    // A operand = V^T: lane (dh = dt*16 + lq, group g) needs V[key][dh] for the 8 keys of its slots, a
+    // column of the row-major LDS tile.  The transposing LDS read of gfx950 delivers exactly that: within
+    // a group of 16 lanes, lane i receives element i % 4 of the 8-byte chunks that lanes 4j + i/4
+    // (j = 0..3) point at (layout checked on the device).  So lane c of the group points at the four
+    // dh values dt*16 + 4*(c%4) .. +3 of key 4g + c/4, and lane i gets keys 4g .. 4g+3 at dh dt*16 + i.
+    const int keyA = kp * 32 + 4 * g + (lq >> 2), keyB = keyA + 16;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const int dh = dt * 16 + lq;
-      union { bf16_t u[8]; uint4 q; } va;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int key = kp * 32 + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
-        const int sw = (dh >> 3) ^ (key & (PPR - 1));
-        va.u[e] = *reinterpret_cast<const bf16_t*>(sV + key * ROWB + sw * 16 + (dh & 7) * 2);
-      }
+      const int dh = dt * 16 + 4 * (lq & 3);
+      const unsigned char* pa = sV + keyA * ROWB + (((dh >> 3) ^ (keyA & (PPR - 1))) * 16) + (dh & 7) * 2;
+      const unsigned char* pb2 = sV + keyB * ROWB + (((dh >> 3) ^ (keyB & (PPR - 1))) * 16) + (dh & 7) * 2;
+      union { short4v h[2]; uint4 q; } va;
+      va.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v*)pa);
+      va.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v*)pb2);
       o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va.q), __builtin_bit_cast(bf16x8_t, pb.q),
                                                       o[dt], 0, 0, 0);
       o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, va.q), __builtin_bit_cast(bf16x8_t, pl.q),
