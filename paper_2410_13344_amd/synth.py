@@ -213,7 +213,8 @@ def paths_to_tree(paths: Sequence[Path]) -> Tuple[List[int], List[int]]:
 def make_tree(name: str, n_heads: int = 4) -> Tuple[List[int], List[int]]:
     """'tiny' = the fixed 16-node tree; 'p63' = 63 generated paths + root = 64 nodes;
     'chain<k>' = a single path of k nodes below the root (rank 0 everywhere); 'bfs<k>x<n>' = the
-    first n nodes of the k-ary tree in breadth-first order."""
+    first n nodes of the k-ary tree in breadth-first order; 'rand<n>s<seed>k<k>' = a seeded random
+    tree of n nodes with at most k children per node (children take ranks 0, 1, ... in order)."""
     if name == "tiny":
         return paths_to_tree(TINY_TREE_PATHS)
     if name == "root":
@@ -221,6 +222,19 @@ def make_tree(name: str, n_heads: int = 4) -> Tuple[List[int], List[int]]:
     if name.startswith("chain"):
         k = int(name[5:])
         return paths_to_tree([tuple([0] * i) for i in range(k + 1)])
+    if name.startswith("rand"):                     # 'rand<n>s<seed>k<k>': n nodes, random shape, at most k children per node
+        n, rest = name[4:].split("s")
+        seed, k = rest.split("k")
+        n, seed, k = int(n), int(seed), int(k)
+        g = _gen(seed, 600_001, "cpu")
+        paths: List[Path] = [()]
+        while len(paths) < n:
+            p = paths[int(torch.randint(0, len(paths), (1,), generator=g))]
+            kids = sum(1 for q in paths if len(q) == len(p) + 1 and q[:-1] == p)
+            if len(p) < n_heads and kids < k:
+                paths.append(p + (kids,))
+        paths.sort(key=lambda t: (len(t), t))
+        return paths_to_tree(paths)
     if name.startswith("bfs"):                      # 'bfs<k>x<n>': the first n nodes of the k-ary tree in breadth-first order
         k, n = (int(v) for v in name[3:].split("x"))
         paths, level = [()], [()]

@@ -464,6 +464,35 @@ def test_tiny_batch_mixed_ar_and_tree_in_one_launch(dtype):
         assert out["T"] == 1 and not rep.failures, f"ar seq {b}: " + "; ".join(rep.failures)
 
 
+@pytest.mark.parametrize("tree", ["root", "chain4", "rand17s1k4", "rand33s2k4", "rand65s3k4", "rand100s4k4", "rand129s5k4"])
+def test_tiny_odd_tree_shapes(tree):
+    """Tree sizes that are no multiple of anything (a lone root, a single chain, random shapes around
+    the 16-, 32-, 64- and 128-row boundaries), bf16 MFMA path, two sequences with different prefixes:
+    every node's token, logits and argmax, acceptance, gate, candidates against the oracle."""
+    pair = H.Pair("tiny", BF16, tree, seed=0, max_batch=2, kv_capacity=384)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    osts = []
+    for b, n_prompt in enumerate((131, 58)):
+        prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=70 + b).numpy()
+        osts.append(orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity))
+    for step in range(2):
+        for b, ost in enumerate(osts):
+            ost["flag"] = 0
+            H.round_oracle_kv(ost, BF16)
+            H.upload_sequence(st, b, ost, BF16)
+        outs = [pair.oracle_step(ost) for ost in osts]
+        pair.engine.verify_step(st, 2)
+        torch.cuda.synchronize()
+        assert int(st.status[0]) == 0
+        for b, (ost, out) in enumerate(zip(osts, outs)):
+            rep = H.compare_step(cfg, out, st, taps, b, pair.T, BF16, ost, tol=H.TOL_BF16_TINY)
+            assert not rep.failures, f"{tree} step {step} seq {b}: " + "; ".join(rep.failures)
+    say(f"  tree {tree}: {pair.T} nodes ok")
+    pair.engine.close()
+
+
 def test_tiny_maximum_batch_and_tree():
     """The largest launch the library takes: 16 sequences, a 192-node tree (three mask words, three
     query blocks and tree chunks), 13 of them running the whole tree and 3 a single row: 2499 packed
