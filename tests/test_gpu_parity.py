@@ -493,6 +493,18 @@ def test_tiny_odd_tree_shapes(tree):
     pair.engine.close()
 
 
+@pytest.mark.parametrize("dtype,attn_mfma", [(F32, 0), (BF16, 1)])
+def test_tiny_head_dim_128_full_tree(dtype, attn_mfma):
+    """The 7B/13B head size (128) and the 64-node tree at a width the oracle can afford for every
+    node: two heads of 128, all 64 rows compared (the full-size tests compare one sampled path)."""
+    say(f"tiny with head_dim 128, 64-node tree, dtype={dtype}")
+    pair = H.Pair("tiny", dtype, "p63", seed=0, max_batch=1, kv_capacity=384, n_heads=2, head_dim=128, topk=6)
+    assert pair.cfg["n_heads"] * pair.cfg["head_dim"] == pair.cfg["d_model"] and pair.T == 64
+    reps = _run_forced_steps(pair, 3, "planted", attn_mfma)
+    assert sum(r.argmax_checked for _, r in reps) > 0
+    pair.engine.close()
+
+
 def test_tiny_maximum_batch_and_tree():
     """The largest launch the library takes: 16 sequences, a 192-node tree (three mask words, three
     query blocks and tree chunks), 13 of them running the whole tree and 3 a single row: 2499 packed
