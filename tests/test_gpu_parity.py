@@ -505,6 +505,53 @@ def test_tiny_head_dim_128_full_tree(dtype, attn_mfma):
     pair.engine.close()
 
 
+def test_graph_replay_equals_eager_launch(tiny_pairs):
+    """bench.py times a HIP-graph replay of the step.  The same step captured once and replayed
+    several times, with eager work and synchronisations between the replays, must reproduce the
+    eager launch bit for bit every time (the library enqueues kernels only, no memset nodes)."""
+    pair = tiny_pairs(BF16)
+    pair.engine.set_param("attn_mfma", 1)
+    taps = pair.taps()
+    ost = _prefilled(pair)
+    H.round_oracle_kv(ost, BF16)
+    st = pair.engine.new_state()
+    H.upload_sequence(st, 0, ost, BF16)
+    snap = {k: getattr(st, k).clone() for k in ("kv", "kv_len", "root_token", "cand", "gate_flag")}
+
+    def restore():
+        for k, v in snap.items():
+            getattr(st, k).copy_(v)
+
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    names = ("kv", "kv_len", "root_token", "cand", "gate_flag", "entropy", "accept_len", "accepted_tokens", "accepted_nodes")
+    eager = {k: getattr(st, k).clone() for k in names}
+    eager_logits = taps.logits.clone()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        restore()
+        pair.engine.verify_step(st, 1, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    restore()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pair.engine.verify_step(st, 1, stream=torch.cuda.current_stream())
+    for rep in range(4):
+        restore()
+        taps.logits.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in names:
+            assert torch.equal(getattr(st, k), eager[k]), (rep, k)
+        assert torch.equal(taps.logits, eager_logits), rep
+        _ = (taps.logits.sum() + st.kv.float().sum()).item()      # eager library work between replays
+    assert int(st.status[0]) == 0
+
+
 def test_tiny_maximum_batch_and_tree():
     """The largest launch the library takes: 16 sequences, a 192-node tree (three mask words, three
     query blocks and tree chunks), 13 of them running the whole tree and 3 a single row: 2499 packed
