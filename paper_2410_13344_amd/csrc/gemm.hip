@@ -60,7 +60,7 @@ __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
 }
 
 template <int MT, int NSUB, int SPLIT>
-__global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_gemm_bf16(const GemmBatch g) {
   if (gemm_skip(g)) return;
   const int rows = g.n_rows ? *g.n_rows : g.rows_static;
   // One-dimensional grid, numbered so that the row blocks of one (column tile, split) have ids 8
@@ -105,6 +105,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
     wp[j] = reinterpret_cast<const uint4*>(P.W) + (size_t)sc * ksteps * 64 + lane;
   }
 
+  // row tiles that hold rows at all (uniform): a launch sized for whole trees may carry a single row
+  const int mt_n = min(MT, (rows - m0 + 15) / 16);
+  const int a_n = 2 * mt_n;                  // staging passes that touch live rows (a pass covers 8 rows)
   f32x4_t acc[MT][NSUB];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -126,48 +129,48 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
   const int a_q = a_pc ^ (a_r0 & 15);                      // (r0 + 8i) & 15 flips bit 3 for odd i
   const int a_dst_e = a_r0 * kLdsRow + a_q * 16, a_dst_o = a_r0 * kLdsRow + (a_q ^ 8) * 16;
 
-#define CERB_A_LD(X, CH)                                                                                      \
+#define CERB_A_LD(X, CH, FULL)                                                                                      \
   {                                                                                                           \
     const bf16_t* sp = a_src + (size_t)(CH) * (KSC * 32);                                                     \
-    if (kApt > 0) X##0 = *reinterpret_cast<const uint4*>(sp);                                                 \
-    if (kApt > 1) X##1 = *reinterpret_cast<const uint4*>(sp + a_step);                                        \
-    if (kApt > 2) X##2 = *reinterpret_cast<const uint4*>(sp + 2 * a_step);                                    \
-    if (kApt > 3) X##3 = *reinterpret_cast<const uint4*>(sp + 3 * a_step);                                    \
-    if (kApt > 4) X##4 = *reinterpret_cast<const uint4*>(sp + 4 * a_step);                                    \
-    if (kApt > 5) X##5 = *reinterpret_cast<const uint4*>(sp + 5 * a_step);                                    \
-    if (kApt > 6) X##6 = *reinterpret_cast<const uint4*>(sp + 6 * a_step);                                    \
-    if (kApt > 7) X##7 = *reinterpret_cast<const uint4*>(sp + 7 * a_step);                                    \
+    if (kApt > 0 && (FULL || 0 < a_n)) X##0 = *reinterpret_cast<const uint4*>(sp);                                                 \
+    if (kApt > 1 && (FULL || 1 < a_n)) X##1 = *reinterpret_cast<const uint4*>(sp + a_step);                                        \
+    if (kApt > 2 && (FULL || 2 < a_n)) X##2 = *reinterpret_cast<const uint4*>(sp + 2 * a_step);                                    \
+    if (kApt > 3 && (FULL || 3 < a_n)) X##3 = *reinterpret_cast<const uint4*>(sp + 3 * a_step);                                    \
+    if (kApt > 4 && (FULL || 4 < a_n)) X##4 = *reinterpret_cast<const uint4*>(sp + 4 * a_step);                                    \
+    if (kApt > 5 && (FULL || 5 < a_n)) X##5 = *reinterpret_cast<const uint4*>(sp + 5 * a_step);                                    \
+    if (kApt > 6 && (FULL || 6 < a_n)) X##6 = *reinterpret_cast<const uint4*>(sp + 6 * a_step);                                    \
+    if (kApt > 7 && (FULL || 7 < a_n)) X##7 = *reinterpret_cast<const uint4*>(sp + 7 * a_step);                                    \
   }
-#define CERB_A_ST(X, BUF)                                                                                     \
+#define CERB_A_ST(X, BUF, FULL)                                                                                     \
   {                                                                                                           \
     unsigned char* dp = lds + (BUF) * kBuf;                                                                   \
-    if (kApt > 0) *reinterpret_cast<uint4*>(dp + a_dst_e) = X##0;                                             \
-    if (kApt > 1) *reinterpret_cast<uint4*>(dp + a_dst_o + 8 * kLdsRow) = X##1;                               \
-    if (kApt > 2) *reinterpret_cast<uint4*>(dp + a_dst_e + 16 * kLdsRow) = X##2;                              \
-    if (kApt > 3) *reinterpret_cast<uint4*>(dp + a_dst_o + 24 * kLdsRow) = X##3;                              \
-    if (kApt > 4) *reinterpret_cast<uint4*>(dp + a_dst_e + 32 * kLdsRow) = X##4;                              \
-    if (kApt > 5) *reinterpret_cast<uint4*>(dp + a_dst_o + 40 * kLdsRow) = X##5;                              \
-    if (kApt > 6) *reinterpret_cast<uint4*>(dp + a_dst_e + 48 * kLdsRow) = X##6;                              \
-    if (kApt > 7) *reinterpret_cast<uint4*>(dp + a_dst_o + 56 * kLdsRow) = X##7;                              \
+    if (kApt > 0 && (FULL || 0 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_e) = X##0;                                             \
+    if (kApt > 1 && (FULL || 1 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_o + 8 * kLdsRow) = X##1;                               \
+    if (kApt > 2 && (FULL || 2 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_e + 16 * kLdsRow) = X##2;                              \
+    if (kApt > 3 && (FULL || 3 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_o + 24 * kLdsRow) = X##3;                              \
+    if (kApt > 4 && (FULL || 4 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_e + 32 * kLdsRow) = X##4;                              \
+    if (kApt > 5 && (FULL || 5 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_o + 40 * kLdsRow) = X##5;                              \
+    if (kApt > 6 && (FULL || 6 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_e + 48 * kLdsRow) = X##6;                              \
+    if (kApt > 7 && (FULL || 7 < a_n)) *reinterpret_cast<uint4*>(dp + a_dst_o + 56 * kLdsRow) = X##7;                              \
   }
 
   uint4 P0, P1, P2, P3, P4, P5, P6, P7, Q0, Q1, Q2, Q3, Q4, Q5, Q6, Q7;
   P0 = P1 = P2 = P3 = P4 = P5 = P6 = P7 = Q0 = Q1 = Q2 = Q3 = Q4 = Q5 = Q6 = Q7 = make_uint4(0, 0, 0, 0);
-  CERB_A_LD(P, 0)
+  CERB_A_LD(P, 0, 0)
   uint4 ring[kRing][NSUB];
 #pragma unroll
   for (int i = 0; i < kRing; ++i)
 #pragma unroll
     for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + i, ks1 - 1) * 64];
-  CERB_A_ST(P, 0)
-  CERB_A_LD(P, min(1, nchunks - 1))
+  CERB_A_ST(P, 0, 0)
+  CERB_A_LD(P, min(1, nchunks - 1), 0)
   __syncthreads();
 
   const int a_row = lane & 15, a_grp = lane >> 4;  // (mt*16 + a_row) & 15 == a_row
 
-#define CERB_GEMM_CHUNK(C, PAR, NEXT2, NEXT1)                                                                                \
+#define CERB_GEMM_CHUNK(C, PAR, NEXT2, NEXT1, FULL)                                                                                \
   {                                                                                                                       \
-    CERB_A_LD(NEXT2, min((C) + 2, nchunks - 1))                                                                           \
+    CERB_A_LD(NEXT2, min((C) + 2, nchunks - 1), FULL)                                                                           \
     const unsigned char* L = lds + ((C) & 1) * kBuf + a_row * kLdsRow;                                                    \
     const int kb = ks0 + (C) * KSC;                                                                                       \
     _Pragma("unroll") for (int s = 0; s < KSC; ++s) {                                                                     \
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
         b[j] = ring[((PAR) * KSC + s) % kRing][j];                                                                        \
         ring[((PAR) * KSC + s) % kRing][j] = wp[j][(size_t)min(kb + s + kRing, ks1 - 1) * 64];                            \
       }                                                                                                                   \
-      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                                 \
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) if (FULL || mt < mt_n) {                                                  \
         const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((s * 4 + a_grp) ^ a_row) * 16));        \
         _Pragma("unroll") for (int j = 0; j < NSUB; ++j) acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(            \
             __builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b[j]), acc[mt][j], 0, 0, 0);                    \
@@ -188,14 +191,25 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const GemmBatch g) {
         }                                                                                                                 \
       }                                                                                                                   \
     }                                                                                                                     \
-    CERB_A_ST(NEXT1, ((C) + 1) & 1)                                                                                       \
+    CERB_A_ST(NEXT1, ((C) + 1) & 1, FULL)                                                                                       \
     __syncthreads();                                                                                                      \
   }
 
-  for (int c = 0; c < nchunks; c += 2) {
-    CERB_GEMM_CHUNK(c, 0, Q, P)               // P holds chunk c+1, Q receives chunk c+2
-    if (c + 1 >= nchunks) break;              // uniform over the workgroup
-    CERB_GEMM_CHUNK(c + 1, 1, P, Q)           // Q holds chunk c+2, P receives chunk c+3
+  // Two copies of the loop: the usual one for a full tile, without a single branch in it, and one
+  // that skips the staging and the MFMAs of row tiles without rows (a launch sized for whole trees
+  // when every sequence took the one-token step).
+  if (mt_n == MT) {
+    for (int c = 0; c < nchunks; c += 2) {
+      CERB_GEMM_CHUNK(c, 0, Q, P, 1)            // P holds chunk c+1, Q receives chunk c+2
+      if (c + 1 >= nchunks) break;              // uniform over the workgroup
+      CERB_GEMM_CHUNK(c + 1, 1, P, Q, 1)        // Q holds chunk c+2, P receives chunk c+3
+    }
+  } else {
+    for (int c = 0; c < nchunks; c += 2) {
+      CERB_GEMM_CHUNK(c, 0, Q, P, 0)
+      if (c + 1 >= nchunks) break;
+      CERB_GEMM_CHUNK(c + 1, 1, P, Q, 0)
+    }
   }
 #undef CERB_GEMM_CHUNK
 #undef CERB_A_LD
