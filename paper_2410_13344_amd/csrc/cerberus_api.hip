@@ -220,7 +220,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   return align_up(b.off, 256);
 }
 
-// Split-K choice: enough workgroups to cover the chip a few times over, whole 256-wide k chunks.
+// Split-K choice: enough workgroups to cover the chip a few times over, whole LDS chunks of k per split.
 void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const* A, const int* lda, size_t lo_off,
                const void* const* W, const int* N, const int* K, int out_rows, bool force_s1) {
   std::memset(&g, 0, sizeof g);
@@ -239,7 +239,10 @@ void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const
       P.K = K[p]; P.S = 1; P.kps = 0;
     } else {
       P.K = kpad(c->cfg, K[p]);
-      const int chunks = P.K / 256;
+      // unit of a split: one LDS chunk of the kernel, 4 k-steps (128 columns of K) with both activation
+      // planes, 8 with one (K is padded to 256, so either divides it)
+      const int unit = c->act_split ? 4 : 8;
+      const int chunks = P.K / (32 * unit);
       int S = force_s1 ? 1 : std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
       S = std::min(S, std::min(c->max_split, chunks));
       // an uneven split leaves some workgroups with less to do and costs a whole extra partial: take
@@ -248,7 +251,7 @@ void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const
         if (chunks % s2 == 0) { S = s2; break; }
       const int cps = ceil_div(chunks, S);
       P.S = ceil_div(chunks, cps);
-      P.kps = cps * 8;
+      P.kps = cps * unit;
     }
     P.out = out;
     out += (size_t)P.S * out_rows * P.N;

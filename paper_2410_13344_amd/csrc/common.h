@@ -70,7 +70,7 @@ struct GemmProb {
   int lda;
   int out_rows;
   int S;          // split-K factor
-  int kps;        // k-steps (of 32) per split, multiple of 8
+  int kps;        // k-steps (of 32) per split, a multiple of the kernel's LDS chunk (4 with both activation planes, 8 with one)
 };
 
 enum { GEMM_MAX_PROB = 8 };

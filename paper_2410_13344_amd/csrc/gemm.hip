@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   static_assert((2 * KSC) % kRing == 0 && (kRing % KSC == 0 || KSC % kRing == 0),
                 "ring slots must be compile-time constants: k-step (chunk parity * KSC + s) lives in slot of that index mod kRing");
   const int ksteps = P.K / 32;               // K is a multiple of 256
-  const int ks0 = split * P.kps;             // kps is a multiple of 8
+  const int ks0 = split * P.kps;             // kps is a multiple of KSC
   const int ks1 = min(ks0 + P.kps, ksteps);
   const int nchunks = (ks1 - ks0) / KSC;
   if (nchunks <= 0) return;                  // uniform over the workgroup
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   // Two copies of the loop: the usual one for a full tile, without a single branch in it, and one
   // that skips the staging and the MFMAs of row tiles without rows (a launch sized for whole trees
   // when every sequence took the one-token step).
-  if (mt_n == MT) {
+  if (MT == 1 || mt_n == MT) {
     for (int c = 0; c < nchunks; c += 2) {
       CERB_GEMM_CHUNK(c, 0, Q, P, 1)            // P holds chunk c+1, Q receives chunk c+2
       if (c + 1 >= nchunks) break;              // uniform over the workgroup
