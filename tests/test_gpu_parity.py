@@ -608,6 +608,34 @@ def test_7b_120_path_tree_sampled_path_matches_oracle(pair_7b):
     pair.engine.close()
 
 
+def test_7b_step_is_bitwise_reproducible(pair_7b):
+    """Split-K partials are summed in a fixed order and nothing uses atomics on floats, so the same
+    state gives the same bits: logits of all 64 nodes, hidden states, candidates, entropy, on three
+    launches of the full-size step (a race between workgroups would show here)."""
+    pair = pair_7b
+    cfg, cap, L = pair.cfg, pair.kv_capacity, 1024
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    kv0 = synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda")
+    cand = synth.make_candidates(cfg, 1, seed=3)[0].cuda()
+    root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    ref = None
+    for rep in range(3):
+        st.kv.copy_(kv0)
+        st.kv_len[0], st.root_token[0], st.gate_flag[0] = L, root, 0
+        st.cand[0] = cand
+        pair.engine.verify_step(st, 1)
+        torch.cuda.synchronize()
+        got = (taps.logits.clone(), taps.h_last.clone(), taps.head_logits.clone(), st.cand.clone(), st.entropy.clone(),
+               st.kv[:, :, :, :, L:L + 8].clone())
+        if ref is None:
+            ref = got
+        else:
+            for a, b in zip(ref, got):
+                assert torch.equal(a, b), rep
+    assert int(st.status[0]) == 0
+
+
 def test_13b_full_size_sampled_path_matches_oracle():
     """configs[3]: 40 layers, d 5120, 40 heads, FFN 13824, five decoding heads, prefix 2048."""
     say("13B: building weights and engine")
