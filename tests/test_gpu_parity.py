@@ -552,6 +552,33 @@ def test_graph_replay_equals_eager_launch(tiny_pairs):
     assert int(st.status[0]) == 0
 
 
+@pytest.mark.parametrize("params", [
+    {"gemm_nsub": 4}, {"gemm_target_wgs": 64}, {"gemm_target_wgs": 4096, "gemm_max_split": 16}, {"gemm_max_split": 1},
+    {"act_split": 0}, {"act_split": 0, "gemm_nsub": 4, "attn_mfma": 0},
+])
+def test_tiny_tuning_knobs_do_not_change_results(params):
+    """Every value of the tuning knobs selects another tiling, split or kernel instance of the same
+    arithmetic (one activation plane instead of two with act_split = 0: bf16-rounded GEMM inputs, still
+    well inside the bf16 bar at this depth)."""
+    pair = H.Pair("tiny", BF16, "p63", seed=0, max_batch=1, kv_capacity=384, topk=6)
+    for k, v in params.items():
+        pair.engine.set_param(k, v)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    ost = orc.prefill(cfg, pair.W, synth.make_token_ids(77, cfg["vocab"], seed=80).numpy(), capacity=pair.kv_capacity)
+    ost["flag"] = 0
+    H.round_oracle_kv(ost, BF16)
+    H.upload_sequence(st, 0, ost, BF16)
+    out = pair.oracle_step(ost)
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    rep = H.compare_step(cfg, out, st, taps, 0, pair.T, BF16, ost, tol=H.TOL_BF16)
+    say(f"  {params}: logits err {rep.max_logit_err:.2e}")
+    assert not rep.failures, f"{params}: " + "; ".join(rep.failures)
+    pair.engine.close()
+
+
 def test_tiny_maximum_batch_and_tree():
     """The largest launch the library takes: 16 sequences, a 192-node tree (three mask words, three
     query blocks and tree chunks), 13 of them running the whole tree and 3 a single row: 2499 packed
