@@ -181,7 +181,14 @@ int cerberus_accept(cerberus_ctx *ctx, const int32_t *node_argmax, const int32_t
 /* Installs (or, with NULL, clears) the taps; the struct is copied.                             */
 int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
 
-/* Tuning knobs, by name; returns CERBERUS_ERR_ARG for an unknown name or a bad value.          */
+/* Tuning knobs, by name; returns CERBERUS_ERR_ARG for an unknown name or a bad value.  None of
+ * them changes what is computed, only how the launches are shaped:
+ *   "gemm_target_wgs" (1..65536, default 768)  workgroups a GEMM launch aims for when choosing split-K
+ *   "gemm_max_split"  (1..16, default 8)       upper bound of the split-K factor
+ *   "gemm_nsub"       (2 or 4, default 2)      16-column slabs per wave (64*nsub columns per workgroup)
+ *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
+ *                                              (bf16-rounded GEMM inputs: faster, less accurate)
+ *   "attn_mfma"       (0 or 1, default 1)      0: plain attention kernel instead of the MFMA one     */
 int cerberus_set_param(cerberus_ctx *ctx, const char *name, int32_t value);
 
 /* Benchmark hook: enqueues back to back, for every layer (or head stage), the GEMM launches of
