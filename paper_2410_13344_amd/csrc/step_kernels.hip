@@ -173,17 +173,36 @@ hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, cons
   return hipGetLastError();
 }
 
+// x[row] = embedding of the row's token, widened to fp32; 512 threads, 8 consecutive elements each
+// per pass (d % 8 == 0)
 template <typename T>
-__global__ __launch_bounds__(256) void k_embed(const T* __restrict__ embed, const RowMap rm, float* __restrict__ x, int d) {
+__global__ __launch_bounds__(512) void k_embed(const T* __restrict__ embed, const RowMap rm, float* __restrict__ x, int d) {
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   const T* e = embed + (size_t)rm.row_tok[r] * d;
-  for (int c = threadIdx.x; c < d; c += 256) x[(size_t)r * d + c] = ld_f(e + c);
+  for (int c = threadIdx.x * 8; c < d; c += 512 * 8) {
+    float v[8];
+    if (sizeof(T) == 2) {
+      const uint4 w = *reinterpret_cast<const uint4*>(e + c);
+      const uint32_t u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(u[i] << 16);
+        v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = ld_f(e + c + i);
+    }
+    float* o = x + (size_t)r * d + c;
+    *reinterpret_cast<float4*>(o) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(o + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
 }
 
 hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, int rows_max, hipStream_t s) {
-  if (D.dtype == 0) hipLaunchKernelGGL((k_embed<float>), dim3(rows_max), dim3(256), 0, s, (const float*)embed, rm, x, D.d);
-  else hipLaunchKernelGGL((k_embed<bf16_t>), dim3(rows_max), dim3(256), 0, s, (const bf16_t*)embed, rm, x, D.d);
+  if (D.dtype == 0) hipLaunchKernelGGL((k_embed<float>), dim3(rows_max), dim3(512), 0, s, (const float*)embed, rm, x, D.d);
+  else hipLaunchKernelGGL((k_embed<bf16_t>), dim3(rows_max), dim3(512), 0, s, (const bf16_t*)embed, rm, x, D.d);
   return hipGetLastError();
 }
 
@@ -440,41 +459,51 @@ hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part,
 // ---------------------------------------------------------------------------------------------
 // Acceptance (tree verification's outcome): walk down from the root while a child carries the
 // token the base model itself produced at the current node; lowest child index on duplicates.
-// One thread per sequence; the walk is at most Hc steps over at most 64 nodes.
+// One wave per sequence; the walk is at most Hc levels.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_accept(const Dims D, const TreeDev tr, const RowMap rm, const int* __restrict__ g,
                                                const int* __restrict__ tok, const cerberus_state st, int* __restrict__ path,
                                                int* __restrict__ last_row, int batch) {
-  const int b = threadIdx.x;
-  if (b >= batch) return;
+  // one wave per sequence: at every level the 64 lanes test 64 candidate children at once and the
+  // lowest matching node index wins (ballot), so a level costs one pass over the tree's nodes
+  const int b = blockIdx.x, lane = threadIdx.x;
   const int Tb = rm.seq_T[b];
-  if (Tb <= 0) { st.accept_len[b] = 0; last_row[b] = -1; return; }
+  if (Tb <= 0) {
+    if (lane == 0) { st.accept_len[b] = 0; last_row[b] = -1; }
+    return;
+  }
   const int row0 = rm.seq_row0[b], W = D.Hc + 1;
-  int cur = 0, a = 1;
-  path[b * W] = 0;
+  int cur = 0, a = 1, mine = 0;   // lane j keeps the j-th node of the path
   while (a < W) {
     const int want = g[row0 + cur];
     int nxt = -1;
-    for (int c = cur + 1; c < Tb; ++c)
-      if (tr.parent[c] == cur && tok[row0 + c] == want) { nxt = c; break; }
+    for (int c0 = cur + 1; c0 < Tb && nxt < 0; c0 += 64) {
+      const int c = c0 + lane;
+      const bool hit = c < Tb && tr.parent[c] == cur && tok[row0 + c] == want;
+      const unsigned long long m = __ballot(hit);
+      if (m) nxt = c0 + __ffsll((long long)m) - 1;
+    }
     if (nxt < 0) break;
-    path[b * W + a] = nxt;
+    if (lane == a) mine = nxt;
     ++a;
     cur = nxt;
   }
-  for (int j = 0; j < a; ++j) {
-    st.accepted_nodes[b * W + j] = path[b * W + j];
-    st.accepted_tokens[b * W + j] = tok[row0 + path[b * W + j]];
+  if (lane < a) {
+    path[b * W + lane] = mine;
+    st.accepted_nodes[b * W + lane] = mine;
+    st.accepted_tokens[b * W + lane] = tok[row0 + mine];
   }
-  st.accept_len[b] = a;
-  st.root_token[b] = g[row0 + cur];
-  st.kv_len[b] = rm.seq_L[b] + a;
-  last_row[b] = row0 + cur;
+  if (lane == 0) {
+    st.accept_len[b] = a;
+    st.root_token[b] = g[row0 + cur];
+    st.kv_len[b] = rm.seq_L[b] + a;
+    last_row[b] = row0 + cur;
+  }
 }
 
 hipError_t launch_accept(const Dims& D, const TreeDev& tr, const RowMap& rm, const int* g, const int* tok,
                          const cerberus_state& st, int* path, int* last_row, int batch, hipStream_t s) {
-  hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, s, D, tr, rm, g, tok, st, path, last_row, batch);
+  hipLaunchKernelGGL(k_accept, dim3(batch), dim3(64), 0, s, D, tr, rm, g, tok, st, path, last_row, batch);
   return hipGetLastError();
 }
 
