@@ -282,7 +282,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2> (QKV, O, gate/up, down, LM head)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 and Bn == 1 and not args.ar else None),
+                     "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 and Bn == 1 and T == 64 and not args.ar else None),
                      "traffic_unit": "MB per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, profiles/)",
                      "algorithmic_MB_per_launch": round(tot_bytes / n_launch / 1e6, 1),
                      "avg_launch_us": round(tot_ms * 1e3 / n_launch, 2), "launches_per_step": n_launch,

@@ -220,45 +220,78 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   return align_up(b.off, 256);
 }
 
-// Split-K choice: enough workgroups to cover the chip a few times over, whole LDS chunks of k per split.
+// Split-K choice: enough workgroups to cover the chip a few times over, whole LDS chunks of k per
+// split.  A launch over more than 64 rows has a workgroup per 64-row block of every (column tile,
+// split) and writes a partial of every row per split, so the split count goes down with the rows:
+// the workgroup target is shared among the row blocks.
+int choose_split(const cerberus_ctx* c, int total_tiles, int chunks, int rows_max) {
+  const int cap = std::min(c->max_split, chunks);
+  if (rows_max <= 64) {
+    int S = std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
+    S = std::min(S, cap);
+    // an uneven split leaves some workgroups with less to do and costs a whole extra partial: take
+    // the next lower split that divides the chunks, if there is one nearby
+    for (int s2 = S; s2 * 5 >= S * 3 && s2 >= 1; --s2)
+      if (chunks % s2 == 0) return s2;
+    return S;
+  }
+  // the split nearest (in ratio) to the ideal one; a split that does not divide the chunks pays for
+  // the idle time of the workgroups with the short last range
+  const double ideal = std::max(1.0, (double)c->target_wgs * 64.0 / ((double)total_tiles * rows_max));
+  int best = 1;
+  double best_cost = std::fabs(std::log(1.0 / ideal));
+  for (int s2 = 2; s2 <= cap; ++s2) {
+    const int cps = ceil_div(chunks, s2);
+    if (ceil_div(chunks, cps) != s2) continue;   // same ranges as a smaller count
+    const double imbalance = (double)cps * s2 / chunks - 1.0;
+    const double cost = std::fabs(std::log((double)s2 / ideal)) + 3.0 * imbalance;
+    if (cost < best_cost) { best = s2; best_cost = cost; }
+  }
+  return best;
+}
+
+// (Re)computes split, tile numbering and partial buffers of a plan for a launch of up to rows_max rows.
+void split_plan(const cerberus_ctx* c, GemmBatch& g, int rows_max) {
+  const int cols = gemm_cols_per_wg(c->cfg.dtype, g.nsub);
+  int total_tiles = 0;
+  for (int p = 0; p < g.n_prob; ++p) total_tiles += ceil_div(g.p[p].N, cols);
+  float* out = c->part;
+  int wg = 0;
+  for (int p = 0; p < g.n_prob; ++p) {
+    GemmProb& P = g.p[p];
+    if (c->cfg.dtype == CERBERUS_F32) {
+      P.S = 1; P.kps = 0;
+    } else {
+      // unit of a split: one LDS chunk of the kernel, 4 k-steps (128 columns of K) with both activation
+      // planes, 8 with one (K is padded to 256, so either divides it)
+      const int unit = g.split ? 4 : 8;
+      const int chunks = P.K / (32 * unit);
+      const int S = g.fixed_s1 ? 1 : choose_split(c, total_tiles, chunks, rows_max);
+      const int cps = ceil_div(chunks, S);
+      P.S = ceil_div(chunks, cps);
+      P.kps = cps * unit;
+    }
+    P.out = out;
+    out += (size_t)P.S * P.out_rows * P.N;
+    g.tile0[p] = wg;
+    wg += ceil_div(P.N, cols) * P.S;
+  }
+  g.tile0[g.n_prob] = wg;
+}
+
 void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const* A, const int* lda, size_t lo_off,
                const void* const* W, const int* N, const int* K, int out_rows, bool force_s1) {
   std::memset(&g, 0, sizeof g);
   g.n_prob = nprob;
   g.nsub = c->gemm_nsub;
   g.split = c->act_split;
-  const int cols = gemm_cols_per_wg(c->cfg.dtype, c->gemm_nsub);
-  int total_tiles = 0;
-  for (int p = 0; p < nprob; ++p) total_tiles += ceil_div(N[p], cols);
-  float* out = c->part;
-  int wg = 0;
+  g.fixed_s1 = force_s1 ? 1 : 0;
   for (int p = 0; p < nprob; ++p) {
     GemmProb& P = g.p[p];
     P.A = A[p]; P.lo_off = lo_off; P.W = W[p]; P.N = N[p]; P.lda = lda[p]; P.out_rows = out_rows;
-    if (c->cfg.dtype == CERBERUS_F32) {
-      P.K = K[p]; P.S = 1; P.kps = 0;
-    } else {
-      P.K = kpad(c->cfg, K[p]);
-      // unit of a split: one LDS chunk of the kernel, 4 k-steps (128 columns of K) with both activation
-      // planes, 8 with one (K is padded to 256, so either divides it)
-      const int unit = c->act_split ? 4 : 8;
-      const int chunks = P.K / (32 * unit);
-      int S = force_s1 ? 1 : std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
-      S = std::min(S, std::min(c->max_split, chunks));
-      // an uneven split leaves some workgroups with less to do and costs a whole extra partial: take
-      // the next lower split that divides the chunks, if there is one nearby
-      for (int s2 = S; s2 * 5 >= S * 3 && s2 >= 1; --s2)
-        if (chunks % s2 == 0) { S = s2; break; }
-      const int cps = ceil_div(chunks, S);
-      P.S = ceil_div(chunks, cps);
-      P.kps = cps * unit;
-    }
-    P.out = out;
-    out += (size_t)P.S * out_rows * P.N;
-    g.tile0[p] = wg;
-    wg += ceil_div(N[p], cols) * P.S;
+    P.K = c->cfg.dtype == CERBERUS_F32 ? K[p] : kpad(c->cfg, K[p]);
   }
-  g.tile0[nprob] = wg;
+  split_plan(c, g, 64);
 }
 
 void build_plans(cerberus_ctx* c) {
@@ -303,9 +336,13 @@ int check_state(const cerberus_ctx* c, const cerberus_state* st, int batch) {
   return CERBERUS_OK;
 }
 
+// Launches a planned GEMM over up to rows_max rows and returns the first problem as launched (its
+// split count and partial buffer are what the consumer of the partials needs).
 int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, int rows_static, int rows_max,
-             const int* skip_flags, int n_skip, hipStream_t s) {
+             const int* skip_flags, int n_skip, hipStream_t s, GemmProb* launched = nullptr) {
   GemmBatch g = plan;
+  if (rows_max > 64) split_plan(c, g, rows_max);
+  if (launched) *launched = g.p[0];
   g.n_rows = n_rows;
   g.rows_static = rows_static;
   g.skip_flags = skip_flags;
@@ -329,12 +366,13 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
   const size_t kv_layer_bytes = (size_t)2 * D.Bmax * D.nH * D.cap * D.dh * c->elem;
   HIP_TRY(launch_embed(D, rm, c->embed, c->x, rows_max, s));
 
-  const GemmProb* prev = nullptr;  // GEMM whose partials are the pending residual
+  GemmProb pd{};                   // GEMM whose partials are the pending residual
+  const GemmProb* prev = nullptr;
   for (int l = 0; l < D.n_layers; ++l) {
     HIP_TRY(launch_add_gain(D, rm, c->x, prev ? prev->out : nullptr, prev ? prev->S : 0,
                             prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, c->ssq, rows_max, s));
-    TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
-    const GemmProb& pq = c->p_qkv[l].p[0];
+    GemmProb pq, po, pg;
+    TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pq));
     void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
     HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, c->ktree, c->vtree,
                            c->ssq, rows_max, s));
@@ -343,20 +381,18 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
     aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
     aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
-    TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
-    const GemmProb& po = c->p_o[l].p[0];
+    TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &po));
     HIP_TRY(launch_add_gain(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, c->ssq, rows_max, s));
-    TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
-    const GemmProb& pg = c->p_gu[l].p[0];
+    TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pg));
     HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, c->ssq, rows_max, s));
-    TRY(run_gemm(c, c->p_down[l], rm.n_rows, 0, rows_max, nullptr, 0, s));
-    prev = &c->p_down[l].p[0];
+    TRY(run_gemm(c, c->p_down[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pd));
+    prev = &pd;
   }
   if (!head) return CERBERUS_OK;
   HIP_TRY(launch_add_rmsnorm(D, rm, c->x, prev->out, prev->S, (size_t)prev->out_rows * prev->N, c->final_norm, c->xn,
                              c->h_last, c->taps.h_last, rows_max, s));
-  TRY(run_gemm(c, c->p_lm, rm.n_rows, 0, rows_max, nullptr, 0, s));
-  const GemmProb& pl = c->p_lm.p[0];
+  GemmProb pl;
+  TRY(run_gemm(c, c->p_lm, rm.n_rows, 0, rows_max, nullptr, 0, s, &pl));
   HIP_TRY(launch_row_argmax(D, rm, pl.out, pl.S, (size_t)pl.out_rows * pl.N, c->g, c->taps, rows_max, s));
 
   return CERBERUS_OK;

@@ -86,6 +86,7 @@ struct GemmBatch {
   int nsub;                      // bf16: 16-column slabs per wave (2 or 4); a workgroup covers 64*nsub columns
   int split;                     // bf16: 1 = multiply the hi and the lo activation plane, 0 = hi only
   int row_blocks;                // bf16: blocks of 64 rows in the launch (set by the launcher)
+  int fixed_s1;                  // host side: the planner keeps split-K off (the consumer reads out[0] as the result)
 };
 
 // launchers (defined next to their kernels)
