@@ -111,6 +111,12 @@ def main() -> int:
     ap.add_argument("--medusa-heads", action="store_true",
                     help="independent d-wide heads (special_block = -1) instead of the linked Cerberus heads")
     ap.add_argument("--ar", action="store_true", help="time the plain auto-regressive step (tree of size 1, no heads)")
+    ap.add_argument("--gate-threshold", type=float, default=None,
+                    help="entropy threshold of the gate (default +inf: the gate always says parallel, so the heads run "
+                         "after every step; -1: it always says auto-regressive and the heads are skipped)")
+    ap.add_argument("--ar-direct", action="store_true",
+                    help="with --ar: call cerberus_ar_step (launches sized for one row per sequence) instead of "
+                         "reaching the step through the gate flag of cerberus_verify_step")
     ap.add_argument("--batch", type=int, default=1, help="sequences per launch (prefix lengths spread over [prefix/2, prefix])")
     ap.add_argument("--mixed", action="store_true", help="with --batch: every third sequence takes the auto-regressive step")
     ap.add_argument("--calib-copy", action="store_true",
@@ -139,7 +145,9 @@ def main() -> int:
     tree_name = args.tree or ("tiny" if name == "tiny" else "p63")
     if tree_name in ("p120", "p150"):
         over["topk"] = 10                              # Section 5.1: top-10 predictions per head for the larger trees
-    cfg = synth.make_config(name, **over)              # entropy_threshold = +inf: gate forced parallel
+    if args.gate_threshold is not None:
+        over["entropy_threshold"] = args.gate_threshold
+    cfg = synth.make_config(name, **over)              # entropy_threshold = +inf unless given: gate forced parallel
     L = args.prefix if args.prefix is not None else {"7b": 1024, "13b": 2048, "tiny": 128}[name]
     parent, rank = synth.make_tree(tree_name, cfg["n_cerb_heads"])
     T = len(parent)
@@ -179,6 +187,8 @@ def main() -> int:
         elif args.decode:
             log_count.zero_()
             eng.decode(st, Bn, args.decode, log_tokens, log_count)
+        elif args.ar_direct:
+            eng.ar_step(st, Bn)
         else:
             eng.verify_step(st, Bn)
 
@@ -257,7 +267,7 @@ def main() -> int:
         alg = dict(per[0])
         for k in ("kv_prefix_read", "tree_kv_write_read", "embedding_rows"):
             alg[k] = sum(q[k] for q in per)
-        if all(flags):
+        if bool((st.gate_flag[:Bn] != 0).all()):   # the gate after the step sent every sequence down the one-token path
             alg["heads"] = 0
         alg["total"] = sum(v for k, v in alg.items() if k != "total")
 
