@@ -646,20 +646,30 @@ hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const f
 // ---------------------------------------------------------------------------------------------
 // Per-head top-k (the heads' token candidates), in the order (value descending, id ascending).
 // Every thread keeps its slice of the row in registers and caches the best entry of its slice that
-// has not been taken yet; a round is one block-wide argmax over those cached entries, after which
-// only the winner's owner rescans its slice for its next best (everyone else's cached entry still
-// comes after the winner in the order).  Sequences whose gate chose the auto-regressive step keep
-// their old candidates.
+// has not been taken yet.  Each wave first lists the topk best entries of its own 64 slices: a
+// round is a wave-wide argmax over the cached entries (no barrier), after which only the winner's
+// owner rescans its slice for its next best (everyone else's cached entry still comes after the
+// winner in the order).  The first wave then merges the waves' sorted lists head by head.
+// Sequences whose gate chose the auto-regressive step keep their old candidates.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void wave_argmax(float& bv, int& bi) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(bv, off, 64);
+    const int oi = __shfl_xor(bi, off, 64);
+    better(bv, bi, ov, oi);
+  }
+}
+
+template <int kG>   // float4 groups per thread: the vocabulary has at most kG * 4096 entries
 __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
                                                int topk) {
-  __shared__ float shv[16];
-  __shared__ int shi[16];
+  __shared__ float cv[16 * CERBERUS_MAX_TOPK];
+  __shared__ int ci[16 * CERBERUS_MAX_TOPK];
   const int i = blockIdx.x, b = blockIdx.y;
   if (st.gate_flag[b] != 0 || a.seq_T[b] <= 0) return;
   const float* lg = a.logits[i] + (size_t)b * V;
-  // float4 groups tid, tid + 1024, ...: up to 16 * 4096 = 65536 vocabulary entries
-  constexpr int kG = 16;
+  // float4 groups tid, tid + 1024, ...
   float4 val[kG];
   // all loads first (clamped, V % 4 == 0), then the entries past the vocabulary become -inf
 #pragma unroll
@@ -691,21 +701,37 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
       }
     }
   };
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   float lv;
   int li;
   scan(INFINITY, -1, lv, li);
   for (int r = 0; r < topk; ++r) {
     float bv = lv;
     int bi = li;
-    block_argmax(bv, bi, shv, shi);
-    if (threadIdx.x == 0) st.cand[((size_t)b * Hc + i) * topk + r] = bi == INT_MAX ? 0 : bi;
+    wave_argmax(bv, bi);
+    if (lane == 0) { cv[wave * topk + r] = bv; ci[wave * topk + r] = bi; }
     if (li == bi && bi != INT_MAX) scan(bv, bi, lv, li);   // ids are unique: this thread owned the winner
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  // lane w < nw walks wave w's list; the best head is the next entry overall
+  int pos = 0;
+  for (int r = 0; r < topk; ++r) {
+    const bool live = (lane < nw) & (pos < topk);
+    const float hv = live ? cv[lane * topk + pos] : -INFINITY;
+    const int hi = live ? ci[lane * topk + pos] : INT_MAX;
+    float bv = hv;
+    int bi = hi;
+    wave_argmax(bv, bi);
+    if (lane == 0) st.cand[((size_t)b * Hc + i) * topk + r] = bi == INT_MAX ? 0 : bi;
+    if (live && hi == bi && bi != INT_MAX) ++pos;
   }
 }
 
 hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& st, const cerberus_taps& tp, int batch,
                        hipStream_t s) {
-  hipLaunchKernelGGL(k_topk, dim3(D.Hc, batch), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.topk);
+  if (D.V <= 8 * 4096) hipLaunchKernelGGL((k_topk<8>), dim3(D.Hc, batch), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.topk);
+  else hipLaunchKernelGGL((k_topk<16>), dim3(D.Hc, batch), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.topk);
   return hipGetLastError();
 }
 
