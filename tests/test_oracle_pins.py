@@ -212,8 +212,7 @@ def test_prompt_in_passes_equals_one_shot_prefill():
 # tree verification: brute force over every root-to-leaf path
 # ---------------------------------------------------------------------------------------
 
-@pytest.fixture(scope="module")
-def tiny_tree_pass():
+def make_tiny_tree_pass():
     cfg, W = tiny()
     parent, rank = synth.make_tree("tiny")
     prompt = synth.make_token_ids(20, cfg["vocab"], seed=1).numpy()
@@ -225,6 +224,11 @@ def tiny_tree_pass():
     cand = st["cand"].copy()
     out = orc.verify_step(cfg, W, parent, rank, st)
     return cfg, W, parent, rank, prompt, root, cand, kv_before, out, st
+
+
+@pytest.fixture(scope="module")
+def tiny_tree_pass():
+    return make_tiny_tree_pass()
 
 
 def test_tree_pass_equals_full_causal_decode_of_every_path(tiny_tree_pass):
@@ -398,6 +402,62 @@ def test_compacted_cache_equals_ar_cache():
     for (K, V), (Kr, Vr) in zip(st["kv"], ref["kv"]):
         assert np.allclose(K[:, :20], Kr[:, :20], atol=1e-9)
         assert np.allclose(V[:, :20], Vr[:, :20], atol=1e-9)
+
+
+def test_gate_and_heads_read_the_last_accepted_position():
+    """Algorithm 1 lines 6-12 act on the hidden state of the newest committed token: after a step
+    that accepted several tokens, entropy and candidates are what a plain causal forward over
+    prompt + committed tokens gives at its last position (not at the tree's root)."""
+    cfg, W = tiny()
+    parent, rank = synth.make_tree("tiny")
+    prompt = synth.make_token_ids(16, cfg["vocab"], seed=14).numpy()
+    ref = orc.prefill(cfg, W, prompt, capacity=64)
+    greedy = orc.greedy_decode(cfg, W, ref["kv"], ref["L"], ref["root"], 6)
+    st = orc.prefill(cfg, W, prompt, capacity=64)
+    cand = np.full((4, 4), -1, dtype=np.int64)
+    cand[0, 0], cand[1, 0] = greedy[1], greedy[2]
+    st["cand"], st["flag"] = cand, 0
+    out = orc.verify_step(cfg, W, parent, rank, st)
+    assert out["accept_len"] == 3
+    seq = np.concatenate([prompt, np.asarray(greedy[:3])])
+    h_t, _ = _torch_causal_forward(cfg, W, seq)
+    h = h_t[-1]
+    P = scipy.special.softmax(h)
+    assert abs(out["entropy"] - scipy.stats.entropy(P, base=2)) < 1e-9
+    want = np.stack([orc.topk_ids(hl, cfg["topk"]) for hl in orc.cerberus_heads(cfg, W["heads"], h)])
+    assert np.array_equal(out["cand"], want)
+    h_root, _ = _torch_causal_forward(cfg, W, seq[:-2])
+    assert not np.array_equal(out["cand"], np.stack(
+        [orc.topk_ids(hl, cfg["topk"]) for hl in orc.cerberus_heads(cfg, W["heads"], h_root[-1])]))
+
+
+def test_prompt_phase_gates_on_its_last_position():
+    """Algorithm 1 lines 4-6: the first gate decision is taken on the prompt's last hidden state.
+    The threshold sits halfway between the entropies of the first and the last position (from the
+    torch forward), so gating on any other position flips the flag."""
+    cfg0, W = tiny()
+    prompt = synth.make_token_ids(16, cfg0["vocab"], seed=16).numpy()
+    h_t, _ = _torch_causal_forward(cfg0, W, prompt)
+    S = [scipy.stats.entropy(scipy.special.softmax(h_t[i]), base=2) for i in (0, len(prompt) - 1)]
+    assert abs(S[0] - S[1]) > 1e-4
+    cfg, _ = tiny(entropy_threshold=float(0.5 * (S[0] + S[1])))
+    st = orc.prefill(cfg, W, prompt, capacity=32)
+    assert st["flag"] == (1 if S[1] > S[0] else 0)
+
+
+def test_heads_are_skipped_when_the_gate_says_auto_regressive():
+    """Algorithm 1 lines 7-8: above the threshold the step ends with the LM head's token alone;
+    the decoding heads are not evaluated and the candidates in the state stay as they were."""
+    cfg, W = tiny(entropy_threshold=-1.0)         # every entropy is above it
+    parent, rank = synth.make_tree("tiny")
+    prompt = synth.make_token_ids(16, cfg["vocab"], seed=15).numpy()
+    st = orc.prefill(cfg, W, prompt, capacity=64)
+    assert st["flag"] == 1 and not st["cand"].any()            # the prompt phase skipped them too
+    old = np.arange(16, dtype=np.int64).reshape(4, 4) + 100
+    st["cand"], st["flag"] = old.copy(), 0
+    out = orc.verify_step(cfg, W, parent, rank, st)
+    assert out["flag"] == 1 and out["head_logits"] is None
+    assert np.array_equal(st["cand"], old) and np.array_equal(out["cand"], old)
 
 
 def test_compaction_is_hazard_free_sequentially():
