@@ -62,6 +62,8 @@ struct cerberus_ctx {
   RowMap rm{};
   double* inv_freq = nullptr;
   int *last_row = nullptr, *path = nullptr, *g = nullptr;
+  float* topk_v = nullptr;   // per-slice candidate lists of the heads' top-k: [Hc][Bmax][TOPK_MAX_PARTS][CERBERUS_MAX_TOPK]
+  int* topk_i = nullptr;
   float *x = nullptr, *h_last = nullptr, *part = nullptr, *attn_po = nullptr, *attn_ml = nullptr, *ssq = nullptr;
   void *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr, *ktree = nullptr, *vtree = nullptr;
   void* hsA[2] = {nullptr, nullptr};
@@ -169,6 +171,8 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->rm.row_tok = b.take<int>(Rmax);
   c->last_row = b.take<int>(B);
   c->path = b.take<int>((size_t)B * (D.Hc + 1));
+  c->topk_v = b.take<float>((size_t)D.Hc * B * TOPK_MAX_PARTS * CERBERUS_MAX_TOPK);
+  c->topk_i = b.take<int>((size_t)D.Hc * B * TOPK_MAX_PARTS * CERBERUS_MAX_TOPK);
   c->g = b.take<int>(Rmax);
   c->x = b.take<float>((size_t)R64 * d);
   c->h_last = b.take<float>((size_t)R64 * d);
@@ -417,6 +421,8 @@ int run_heads(cerberus_ctx* c, const cerberus_state* st, int batch, hipStream_t 
   TRY(run_gemm(c, c->p_fc, nullptr, batch, batch, st->gate_flag, batch, s));
   TopkArgs ta{};
   ta.seq_T = rm.seq_T;
+  ta.part_v = c->topk_v;
+  ta.part_i = c->topk_i;
   for (int i = 0; i < D.Hc; ++i) ta.logits[i] = c->p_fc.p[i].out;
   HIP_TRY(launch_topk(D, ta, *st, c->taps, batch, s));
   return CERBERUS_OK;

@@ -27,9 +27,12 @@ struct ResFinishArgs {
   int width[CERBERUS_MAX_HEADS];
 };
 
+enum { TOPK_MAX_PARTS = 16 };               // vocabulary slices of 4096 entries: up to 65536
 struct TopkArgs {
   const float* logits[CERBERUS_MAX_HEADS];  // head i: [16][V]
   const int* seq_T;                         // [B] rows of each sequence this step (0: sat out)
+  float* part_v;                            // [Hc][B][TOPK_MAX_PARTS][CERBERUS_MAX_TOPK] best entries of every slice, in order
+  int* part_i;
 };
 
 hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, const cerberus_state& st,

@@ -645,11 +645,11 @@ hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const f
 
 // ---------------------------------------------------------------------------------------------
 // Per-head top-k (the heads' token candidates), in the order (value descending, id ascending).
-// Every thread keeps its slice of the row in registers and caches the best entry of its slice that
-// has not been taken yet.  Each wave first lists the topk best entries of its own 64 slices: a
-// round is a wave-wide argmax over the cached entries (no barrier), after which only the winner's
-// owner rescans its slice for its next best (everyone else's cached entry still comes after the
-// winner in the order).  The first wave then merges the waves' sorted lists head by head.
+// Two launches.  k_topk_slice: a workgroup owns 4096 consecutive vocabulary entries of one (head,
+// sequence), four per thread.  Each wave lists the topk best of its 256 entries (a round is a
+// wave-wide argmax over the lanes' best entries not taken yet, no barrier; only the winner's lane
+// looks for its next one), the first wave merges the 16 sorted lists and writes the slice's list.
+// k_topk_merge: one wave per (head, sequence) merges the slices' lists head by head.
 // Sequences whose gate chose the auto-regressive step keep their old candidates.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void wave_argmax(float& bv, int& bi) {
@@ -661,47 +661,48 @@ __device__ __forceinline__ void wave_argmax(float& bv, int& bi) {
   }
 }
 
-template <int kG>   // float4 groups per thread: the vocabulary has at most kG * 4096 entries
-__global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
-                                               int topk) {
+// Merge of n <= 64 lists sorted in the order, list w at lv/li[w * stride ..]: lane w walks list w;
+// the best of the lists' heads is the next entry overall.  Calls out(r, id) on lane 0.
+template <typename Out>
+__device__ __forceinline__ void merge_lists(const float* lv, const int* li, int n, int stride, int topk, int lane, Out out) {
+  int pos = 0;
+  for (int r = 0; r < topk; ++r) {
+    const bool live = (lane < n) & (pos < topk);
+    const float hv = live ? lv[lane * stride + pos] : -INFINITY;
+    const int hi = live ? li[lane * stride + pos] : INT_MAX;
+    float bv = hv;
+    int bi = hi;
+    wave_argmax(bv, bi);
+    if (lane == 0) out(r, bv, bi);
+    if (live && hi == bi && bi != INT_MAX) ++pos;   // ids are unique: this lane's list held the winner
+  }
+}
+
+__global__ __launch_bounds__(1024) void k_topk_slice(const TopkArgs a, const cerberus_state st, const cerberus_taps tp, int V, int Hc,
+                                                     int B, int topk) {
   __shared__ float cv[16 * CERBERUS_MAX_TOPK];
   __shared__ int ci[16 * CERBERUS_MAX_TOPK];
-  const int i = blockIdx.x, b = blockIdx.y;
+  const int i = blockIdx.x, b = blockIdx.y, part = blockIdx.z;
   if (st.gate_flag[b] != 0 || a.seq_T[b] <= 0) return;
   const float* lg = a.logits[i] + (size_t)b * V;
-  // float4 groups tid, tid + 1024, ...
-  float4 val[kG];
-  // all loads first (clamped, V % 4 == 0), then the entries past the vocabulary become -inf
-#pragma unroll
-  for (int k = 0; k < kG; ++k) {
-    const int v = (k * 1024 + threadIdx.x) * 4;
-    val[k] = *reinterpret_cast<const float4*>(lg + min(v, V - 4));
+  const int v0 = (part * 1024 + threadIdx.x) * 4;         // V % 4 == 0
+  float e[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  if (v0 < V) {
+    const float4 val = *reinterpret_cast<const float4*>(lg + v0);
+    if (tp.head_logits) *reinterpret_cast<float4*>(tp.head_logits + ((size_t)b * Hc + i) * V + v0) = val;
+    e[0] = val.x; e[1] = val.y; e[2] = val.z; e[3] = val.w;
   }
-#pragma unroll
-  for (int k = 0; k < kG; ++k) {
-    const int v = (k * 1024 + threadIdx.x) * 4;
-    if (v < V) {
-      if (tp.head_logits) *reinterpret_cast<float4*>(tp.head_logits + ((size_t)b * Hc + i) * V + v) = val[k];
-    } else {
-      val[k] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-    }
-  }
-  // best entry of this thread's slice strictly after (pv, pi) in the order; (-inf, INT_MAX) if none
+  // best of this lane's entries strictly after (pv, pi) in the order; (-inf, INT_MAX) if none
   auto scan = [&](float pv, int pi, float& lv, int& li) {
     lv = -INFINITY;
     li = INT_MAX;
 #pragma unroll
-    for (int k = 0; k < kG; ++k) {
-      const int v = (k * 1024 + threadIdx.x) * 4;
-      const float e[4] = {val[k].x, val[k].y, val[k].z, val[k].w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const bool el = (v < V) & ((e[j] < pv) | ((e[j] == pv) & (v + j > pi)));
-        better(lv, li, el ? e[j] : -INFINITY, el ? v + j : INT_MAX);
-      }
+    for (int j = 0; j < 4; ++j) {
+      const bool el = (v0 < V) & ((e[j] < pv) | ((e[j] == pv) & (v0 + j > pi)));
+      better(lv, li, el ? e[j] : -INFINITY, el ? v0 + j : INT_MAX);
     }
   };
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float lv;
   int li;
   scan(INFINITY, -1, lv, li);
@@ -710,28 +711,29 @@ __global__ __launch_bounds__(1024) void k_topk(const TopkArgs a, const cerberus_
     int bi = li;
     wave_argmax(bv, bi);
     if (lane == 0) { cv[wave * topk + r] = bv; ci[wave * topk + r] = bi; }
-    if (li == bi && bi != INT_MAX) scan(bv, bi, lv, li);   // ids are unique: this thread owned the winner
+    if (li == bi && bi != INT_MAX) scan(bv, bi, lv, li);
   }
   __syncthreads();
   if (wave != 0) return;
-  // lane w < nw walks wave w's list; the best head is the next entry overall
-  int pos = 0;
-  for (int r = 0; r < topk; ++r) {
-    const bool live = (lane < nw) & (pos < topk);
-    const float hv = live ? cv[lane * topk + pos] : -INFINITY;
-    const int hi = live ? ci[lane * topk + pos] : INT_MAX;
-    float bv = hv;
-    int bi = hi;
-    wave_argmax(bv, bi);
-    if (lane == 0) st.cand[((size_t)b * Hc + i) * topk + r] = bi == INT_MAX ? 0 : bi;
-    if (live && hi == bi && bi != INT_MAX) ++pos;
-  }
+  float* pv = a.part_v + (((size_t)i * B + b) * TOPK_MAX_PARTS + part) * CERBERUS_MAX_TOPK;
+  int* pi = a.part_i + (((size_t)i * B + b) * TOPK_MAX_PARTS + part) * CERBERUS_MAX_TOPK;
+  merge_lists(cv, ci, 16, topk, topk, lane, [&](int r, float v, int id) { pv[r] = v; pi[r] = id; });
+}
+
+__global__ __launch_bounds__(64) void k_topk_merge(const TopkArgs a, const cerberus_state st, int Hc, int B, int topk, int parts) {
+  const int i = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+  if (st.gate_flag[b] != 0 || a.seq_T[b] <= 0) return;
+  const float* pv = a.part_v + ((size_t)i * B + b) * TOPK_MAX_PARTS * CERBERUS_MAX_TOPK;
+  const int* pi = a.part_i + ((size_t)i * B + b) * TOPK_MAX_PARTS * CERBERUS_MAX_TOPK;
+  int* cand = st.cand + ((size_t)b * Hc + i) * topk;
+  merge_lists(pv, pi, parts, CERBERUS_MAX_TOPK, topk, lane, [&](int r, float, int id) { cand[r] = id == INT_MAX ? 0 : id; });
 }
 
 hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& st, const cerberus_taps& tp, int batch,
                        hipStream_t s) {
-  if (D.V <= 8 * 4096) hipLaunchKernelGGL((k_topk<8>), dim3(D.Hc, batch), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.topk);
-  else hipLaunchKernelGGL((k_topk<16>), dim3(D.Hc, batch), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.topk);
+  const int parts = (D.V + 4095) / 4096;   // V <= 65536
+  hipLaunchKernelGGL(k_topk_slice, dim3(D.Hc, batch, parts), dim3(1024), 0, s, a, st, tp, D.V, D.Hc, D.Bmax, D.topk);
+  hipLaunchKernelGGL(k_topk_merge, dim3(D.Hc, batch), dim3(64), 0, s, a, st, D.Hc, D.Bmax, D.topk, parts);
   return hipGetLastError();
 }
 
