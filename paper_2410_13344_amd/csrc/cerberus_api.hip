@@ -402,11 +402,16 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
   return CERBERUS_OK;
 }
 
+// the gate launch also writes the heads' stage-0 state (the gated row)
+HeadsPrep heads_prep(const cerberus_ctx* c) {
+  const Dims& D = c->D;
+  return HeadsPrep{c->hsF[0], c->hsA[0], D.dtype == CERBERUS_BF16 ? (size_t)D.Hc * 16 * 2 * D.d : 0, D.Hc, D.sb};
+}
+
 // heads: skipped on the device when every sequence's gate chose the auto-regressive step
 int run_heads(cerberus_ctx* c, const cerberus_state* st, int batch, hipStream_t s) {
   const Dims& D = c->D;
   const RowMap& rm = c->rm;
-  HIP_TRY(launch_heads_prepare(D, c->h_last, c->last_row, c->hsF[0], c->hsA[0], batch, s));
   for (int st_i = 0; st_i < D.R; ++st_i) {
     TRY(run_gemm(c, c->p_res[st_i], nullptr, batch, batch, st->gate_flag, batch, s));
     ResFinishArgs ra{};
@@ -441,7 +446,7 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
   HIP_TRY(launch_accept(D, c->tree, rm, c->g, rm.row_tok, *st, c->path, c->last_row, batch, s));
   if (mode != ASSEMBLE_FORCE_AR) HIP_TRY(launch_compact(D, rm, *st, c->path, batch, s));
   HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, c->taps.forced_gate_hidden, rm.seq_T, batch, st->entropy,
-                      st->gate_flag, s));
+                      st->gate_flag, heads_prep(c), D.dtype, s));
   return run_heads(c, st, batch, s);
 }
 
@@ -464,7 +469,8 @@ int run_prompt(cerberus_ctx* c, const cerberus_state* st, int batch, int seq, co
     TRY(forward_rows(c, st, batch, n, c->chain, last, s));
     HIP_TRY(launch_prompt_commit(rm, *st, c->g, c->last_row, batch, seq, last ? 1 : 0, s));
     if (last) {
-      HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, nullptr, rm.seq_T, batch, st->entropy, st->gate_flag, s));
+      HIP_TRY(launch_gate(D.d, D.threshold, c->h_last, c->last_row, nullptr, rm.seq_T, batch, st->entropy, st->gate_flag,
+                          heads_prep(c), D.dtype, s));
       TRY(run_heads(c, st, batch, s));
     }
   }
@@ -642,7 +648,7 @@ int cerberus_gate(cerberus_ctx* ctx, const float* hidden, int32_t rows, float* e
   if (!ctx || !hidden || !entropy_out || !flag_out) return fail(CERBERUS_ERR_ARG, "null argument");
   if (rows < 0) return fail(CERBERUS_ERR_ARG, "rows < 0");
   if (rows == 0) return CERBERUS_OK;
-  HIP_TRY(launch_gate(ctx->D.d, ctx->D.threshold, hidden, nullptr, nullptr, nullptr, rows, entropy_out, flag_out,
+  HIP_TRY(launch_gate(ctx->D.d, ctx->D.threshold, hidden, nullptr, nullptr, nullptr, rows, entropy_out, flag_out, HeadsPrep{}, ctx->D.dtype,
                       reinterpret_cast<hipStream_t>(stream)));
   return CERBERUS_OK;
 }

@@ -59,10 +59,15 @@ hipError_t launch_compact(const Dims& D, const RowMap& rm, const cerberus_state&
                           hipStream_t s);
 // entropy of `rows` vectors: vector r is forced[r] if forced != nullptr, else base[row_index ? row_index[r] : r];
 // rows with seq_T[r] <= 0 (when seq_T != nullptr) are left untouched.
+// Seeding of the decoding heads' stage-0 state by the gate launch; hsF == nullptr: none.
+struct HeadsPrep {
+  float* hsF;     // [Hc][16][2d] fp32 state
+  void* hsA;      // same as the GEMM input type (bf16: lo plane lo_off elements later)
+  size_t lo_off;
+  int Hc, sb;     // number of heads; index of the special block
+};
 hipError_t launch_gate(int d, float threshold, const float* base, const int* row_index, const float* forced,
-                       const int* seq_T, int rows, float* entropy, int* flag, hipStream_t s);
-hipError_t launch_heads_prepare(const Dims& D, const float* h_last, const int* last_row, float* hsF, void* hsA, int batch,
-                                hipStream_t s);
+                       const int* seq_T, int rows, float* entropy, int* flag, const HeadsPrep& hp, int dtype, hipStream_t s);
 hipError_t launch_resblock_finish(const Dims& D, const ResFinishArgs& a, const float* curF, float* nxtF, void* nxtA,
                                   int link_next, int batch, hipStream_t s);
 hipError_t launch_topk(const Dims& D, const TopkArgs& a, const cerberus_state& st, const cerberus_taps& tp, int batch,

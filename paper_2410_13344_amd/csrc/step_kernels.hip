@@ -545,29 +545,82 @@ hipError_t launch_compact(const Dims& D, const RowMap& rm, const cerberus_state&
 // flag = 1 (auto-regressive) iff S > T; equality and only equality-or-below keeps the parallel
 // path, and a NaN entropy takes the auto-regressive one.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_gate(int d, float threshold, const float* __restrict__ base,
-                                              const int* __restrict__ row_index, const float* __restrict__ forced,
-                                              const int* __restrict__ seq_T, float* __restrict__ entropy, int* __restrict__ flag) {
-  __shared__ float shf[4];
-  __shared__ double shd[4];
+// One workgroup of 1024 threads per row keeps the row in registers (d <= 8192, d % 4 == 0): one pass
+// over memory, one block-wide max and one block-wide sum of the three accumulators.
+// With `hp`, the same launch also seeds the decoding heads: the row the gate looks at (the last
+// accepted node's hidden state, Section 4.1) becomes the stage-0 state of every head, and where the
+// first stage is the special block, [d..2d) of head i >= 1 as well (head i-1's state is the same
+// vector there).  A sequence that sat the step out gets a zero state and no gate decision.
+template <typename T>
+__global__ __launch_bounds__(1024) void k_gate(int d, float threshold, const float* __restrict__ base,
+                                               const int* __restrict__ row_index, const float* __restrict__ forced,
+                                               const int* __restrict__ seq_T, float* __restrict__ entropy, int* __restrict__ flag,
+                                               const HeadsPrep hp) {
+  __shared__ float shf[16];
+  __shared__ double shd[3][16];
   const int r = blockIdx.x;
-  if (seq_T && seq_T[r] <= 0) return;
-  const float* h = forced ? forced + (size_t)r * d : base + (size_t)(row_index ? row_index[r] : r) * d;
-  float m = -INFINITY;
-  bool bad = false;
-  for (int c = threadIdx.x; c < d; c += 256) { m = fmaxf(m, h[c]); bad = bad || (h[c] != h[c]); }
-  m = block_max(m, shf);
-  double Z = 0.0, A = 0.0;
-  for (int c = threadIdx.x; c < d; c += 256) {
-    const float z = h[c] - m;
-    const float e = expf(z);
-    Z += (double)e;
-    if (e > 0.f) A += (double)e * (double)z;
+  const bool sat_out = seq_T && seq_T[r] <= 0;
+  const int ri = row_index ? row_index[r] : r;
+  const float* hb = base + (size_t)max(ri, 0) * d;
+  const float* h = forced ? forced + (size_t)r * d : hb;
+  float4 v[2];
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int c = (it * 1024 + threadIdx.x) * 4;
+    v[it] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    if (c < d) {
+      v[it] = *reinterpret_cast<const float4*>(h + c);
+      if (hp.hsF) {
+        float4 s = forced ? *reinterpret_cast<const float4*>(hb + c) : v[it];
+        if (sat_out || ri < 0) s = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float e[4] = {s.x, s.y, s.z, s.w};
+        const int ld = 2 * d;
+        for (int i = 0; i < hp.Hc; ++i) {
+          const size_t o = ((size_t)i * 16 + r) * ld + c;
+          *reinterpret_cast<float4*>(hp.hsF + o) = s;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) st_a(reinterpret_cast<T*>(hp.hsA) + o + j, hp.lo_off, e[j]);
+          if (hp.sb == 0 && i >= 1) {
+            *reinterpret_cast<float4*>(hp.hsF + o + d) = s;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st_a(reinterpret_cast<T*>(hp.hsA) + o + d + j, hp.lo_off, e[j]);
+          }
+        }
+      }
+    }
   }
-  Z = block_sum(Z, shd);
-  A = block_sum(A, shd);
-  const double nbad = block_sum(bad ? 1.0 : 0.0, shd);
+  if (sat_out) return;   // uniform over the workgroup
+  float m = fmaxf(fmaxf(fmaxf(v[0].x, v[0].y), fmaxf(v[0].z, v[0].w)), fmaxf(fmaxf(v[1].x, v[1].y), fmaxf(v[1].z, v[1].w)));
+  m = block_max(m, shf);
+  double Z = 0.0, A = 0.0, nbad = 0.0;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const int c = (it * 1024 + threadIdx.x) * 4;
+    if (c < d) {
+      const float e4[4] = {v[it].x, v[it].y, v[it].z, v[it].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float z = e4[j] - m;
+        const float e = expf(z);
+        Z += (double)e;
+        if (e > 0.f) A += (double)e * (double)z;
+        if (e4[j] != e4[j]) nbad += 1.0;
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    Z += __shfl_xor(Z, off, 64);
+    A += __shfl_xor(A, off, 64);
+    nbad += __shfl_xor(nbad, off, 64);
+  }
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { shd[0][wave] = Z; shd[1][wave] = A; shd[2][wave] = nbad; }
+  __syncthreads();
   if (threadIdx.x == 0) {
+    Z = A = nbad = 0.0;
+    for (int w = 0; w < 16; ++w) { Z += shd[0][w]; A += shd[1][w]; nbad += shd[2][w]; }
     double S = (log(Z) - A / Z) / 0.6931471805599453;
     if (nbad > 0.0) S = NAN;
     entropy[r] = (float)S;
@@ -576,8 +629,11 @@ __global__ __launch_bounds__(256) void k_gate(int d, float threshold, const floa
 }
 
 hipError_t launch_gate(int d, float threshold, const float* base, const int* row_index, const float* forced,
-                       const int* seq_T, int rows, float* entropy, int* flag, hipStream_t s) {
-  hipLaunchKernelGGL(k_gate, dim3(rows), dim3(256), 0, s, d, threshold, base, row_index, forced, seq_T, entropy, flag);
+                       const int* seq_T, int rows, float* entropy, int* flag, const HeadsPrep& hp, int dtype, hipStream_t s) {
+  if (dtype == 0)
+    hipLaunchKernelGGL((k_gate<float>), dim3(rows), dim3(1024), 0, s, d, threshold, base, row_index, forced, seq_T, entropy, flag, hp);
+  else
+    hipLaunchKernelGGL((k_gate<bf16_t>), dim3(rows), dim3(1024), 0, s, d, threshold, base, row_index, forced, seq_T, entropy, flag, hp);
   return hipGetLastError();
 }
 
@@ -586,31 +642,6 @@ hipError_t launch_gate(int d, float threshold, const float* base, const int* row
 // where the coming stage is the special block, [d..2d) of head i holds head i-1's state, so the
 // stage's GEMM simply sees the concatenation (own state first).
 // ---------------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void k_heads_prepare(const Dims D, const float* __restrict__ h_last,
-                                                       const int* __restrict__ last_row, float* __restrict__ hsF,
-                                                       T* __restrict__ hsA, size_t lo_off) {
-  const int b = blockIdx.x;
-  const int lr = last_row[b];
-  const int d = D.d, ld = 2 * d;
-  for (int c = threadIdx.x; c < d; c += 256) {
-    const float v = lr >= 0 ? h_last[(size_t)lr * d + c] : 0.f;
-    for (int i = 0; i < D.Hc; ++i) {
-      const size_t o = ((size_t)i * 16 + b) * ld + c;
-      hsF[o] = v;
-      st_a(hsA + o, lo_off, v);
-      if (D.sb == 0 && i >= 1) { hsF[o + d] = v; st_a(hsA + o + d, lo_off, v); }
-    }
-  }
-}
-
-hipError_t launch_heads_prepare(const Dims& D, const float* h_last, const int* last_row, float* hsF, void* hsA, int batch,
-                                hipStream_t s) {
-  if (D.dtype == 0) hipLaunchKernelGGL((k_heads_prepare<float>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (float*)hsA, (size_t)0);
-  else hipLaunchKernelGGL((k_heads_prepare<bf16_t>), dim3(batch), dim3(256), 0, s, D, h_last, last_row, hsF, (bf16_t*)hsA, (size_t)D.Hc * 16 * 2 * D.d);
-  return hipGetLastError();
-}
-
 // Resblock tail: Output = SiLU((W h + b) + h) from the GEMM partials of W h (Section 4.1).
 template <typename T>
 __global__ __launch_bounds__(256) void k_resblock_finish(const ResFinishArgs a, const float* __restrict__ curF,
