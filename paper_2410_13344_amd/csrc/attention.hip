@@ -81,9 +81,8 @@ __global__ __launch_bounds__(64) void k_attn_simple(const AttnArgs a) {
 //                    row-major LDS tile with transposing reads, in the same slot order.
 // Writes unnormalised partial outputs with (max, sum) per query; k_attn_combine merges the chunks.
 // ---------------------------------------------------------------------------------------------
-template <int DH>
+template <int DH, int CK>   // CK: committed cache rows per workgroup, 128 or 256
 __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
-  constexpr int CK = 128;
   constexpr int PPR = DH / 8;   // 16-byte pieces per row
   constexpr int KS = DH / 32;
   constexpr int DT = DH / 16;
@@ -98,7 +97,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   if (Tb <= 0 || qb * 64 >= Tb) return;
   // The last tc_max workgroups of a (head, sequence, query block) take the tree chunks: 64 of the
   // step's own rows each, read from the hi + lo side planes (LDS rows 0..63 = hi, 64..127 = lo of
-  // the same key).  The others take 128 committed cache rows each.
+  // the same key; rows 128.. stay unused when CK = 256).  The others take CK committed cache rows each.
   const int tci = (int)blockIdx.x - ((int)gridDim.x - a.tc_max);   // >= 0: index of the tree chunk
   const bool tree = tci >= 0;
   const int nprefix = (L + CK - 1) / CK;
@@ -123,8 +122,9 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     rstride = DH;
     nvalid = min(CK, L - key0);                    // >= 1: the block index is below ceil(L / CK)
   }
-  const size_t lo_plane = tree ? a.q_lo_off : 0;   // LDS rows 64.. of the tree chunk: lo halves of rows 0..63
+  const size_t lo_plane = tree ? a.q_lo_off : 0;   // LDS rows 64..127 of the tree chunk: lo halves of rows 0..63
   const int rmask = tree ? 63 : CK - 1;
+  const int nkt = tree ? 8 : CK / 16;              // 16-key tiles in use (uniform)
   constexpr int NI = CK * PPR / 256;
   uint4 kk[NI], vv[NI];
 #pragma unroll
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     const int i = it * 256 + threadIdx.x;
     const int key = i / PPR, pc = i % PPR;
     const int m = key & rmask;
-    const size_t off = (size_t)min(m, nvalid - 1) * rstride + ((key & ~rmask) ? lo_plane : 0);
+    const size_t off = (size_t)min(m, nvalid - 1) * rstride + ((key & 64 & ~rmask) ? lo_plane : 0);
     kk[it] = reinterpret_cast<const uint4*>(Kb + off)[pc];
     vv[it] = reinterpret_cast<const uint4*>(Vb + off)[pc];
   }
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   for (int it = 0; it < NI; ++it) {
     const int i = it * 256 + threadIdx.x;
     const int key = i / PPR, pc = i % PPR;
-    const unsigned ok = (key & rmask) < nvalid ? 0xffffffffu : 0u;   // rows that do not exist are staged as zeros
+    const unsigned ok = (((key & rmask) < nvalid) & (key < nkt * 16)) ? 0xffffffffu : 0u;   // rows that do not exist are staged as zeros
     const int sw = pc ^ (key & (PPR - 1));
     *reinterpret_cast<uint4*>(sK + key * ROWB + sw * 16) = make_uint4(kk[it].x & ok, kk[it].y & ok, kk[it].z & ok, kk[it].w & ok);
     *reinterpret_cast<uint4*>(sV + key * ROWB + sw * 16) = make_uint4(vv[it].x & ok, vv[it].y & ok, vv[it].z & ok, vv[it].w & ok);
@@ -171,6 +171,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
     const int key = kt * 16 + lq;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
+      if (CK > 128 && kt >= nkt) break;
       const int sw = (ks * 4 + g) ^ (key & (PPR - 1));
       const uint4 kf = *reinterpret_cast<const uint4*>(sK + key * ROWB + sw * 16);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf), __builtin_bit_cast(bf16x8_t, qf[ks]),
@@ -223,6 +224,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const AttnArgs a) {
   for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kp = 0; kp < CK / 32; ++kp) {
+    if (CK > 128 && 2 * kp >= nkt) break;
     union { bf16_t u[8]; uint4 q; } pb, pl;   // probabilities as hi + lo bf16, like every GEMM input
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(DH) void k_attn_combine(const AttnArgs a) {
   const int r = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
   if (r >= *a.rm.n_rows) return;
   const int b = a.rm.row_seq[r], node = a.rm.row_node[r];
-  const int nch = (a.rm.seq_L[b] + 127) / 128 + (a.rm.seq_T[b] + 63) / 64;   // committed-row chunks + tree chunks
+  const int nch = (a.rm.seq_L[b] + a.chunk - 1) / a.chunk + (a.rm.seq_T[b] + 63) / 64;   // committed-row chunks + tree chunks
   const size_t base = (((size_t)b * a.nH + h) * a.n_chunks_max) * a.Tpad + node;
   constexpr int NB = 8;
   float M = -INFINITY, num = 0.f, den = 0.f;
@@ -317,13 +319,17 @@ hipError_t launch_attention(const AttnArgs& a, int dtype, int use_mfma, hipStrea
     }
     return hipGetLastError();
   }
-  dim3 grid(a.n_chunks_max, a.nH, a.batch * a.tc_max);   // x: ceil(cap / 128) prefix chunks, then tc_max tree chunks; z: (sequence, query block)
+  if (a.chunk != 128 && a.chunk != 256) return hipErrorInvalidValue;
+  if (a.n_chunks_max != (a.cap + a.chunk - 1) / a.chunk + a.tc_max) return hipErrorInvalidValue;
+  dim3 grid(a.n_chunks_max, a.nH, a.batch * a.tc_max);   // x: ceil(cap / chunk) prefix chunks, then tc_max tree chunks; z: (sequence, query block)
   dim3 cgrid(a.rows_max, a.nH);
   if (a.dh == 64) {
-    hipLaunchKernelGGL((k_attn_mfma<64>), grid, dim3(256), 0, s, a);
+    if (a.chunk == 128) hipLaunchKernelGGL((k_attn_mfma<64, 128>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((k_attn_mfma<64, 256>), grid, dim3(256), 0, s, a);
     hipLaunchKernelGGL((k_attn_combine<64>), cgrid, dim3(64), 0, s, a);
   } else {
-    hipLaunchKernelGGL((k_attn_mfma<128>), grid, dim3(256), 0, s, a);
+    if (a.chunk == 128) hipLaunchKernelGGL((k_attn_mfma<128, 128>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((k_attn_mfma<128, 256>), grid, dim3(256), 0, s, a);
     hipLaunchKernelGGL((k_attn_combine<128>), cgrid, dim3(128), 0, s, a);
   }
   return hipGetLastError();

@@ -82,7 +82,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1, attn_chunk = 128;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
   void* workspace = nullptr;
@@ -383,7 +383,8 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
     AttnArgs aa{};
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
     aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
-    aa.chunk = 128; aa.n_chunks_max = c->n_chunks_max; aa.rows_max = rows_max; aa.status = st->status;
+    aa.chunk = c->attn_chunk; aa.n_chunks_max = ceil_div(D.cap, c->attn_chunk) + aa.tc_max;   // <= c->n_chunks_max, which sized the partial buffers
+    aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &po));
     HIP_TRY(launch_add_gain(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, c->ssq, rows_max, s));
@@ -705,6 +706,9 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
   if (n == "attn_mfma") {
     if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "attn_mfma must be 0 or 1");
     ctx->use_mfma_attn = value;
+  } else if (n == "attn_chunk") {
+    if (value != 128 && value != 256) return fail(CERBERUS_ERR_ARG, "attn_chunk must be 128 or 256");
+    ctx->attn_chunk = value;
   } else if (n == "gemm_target_wgs") {
     if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "gemm_target_wgs out of 1..65536");
     ctx->target_wgs = value;
