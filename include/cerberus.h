@@ -187,8 +187,8 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  *   "gemm_max_split"  (1..16, default 8)       upper bound of the split-K factor
  *   "gemm_nsub"       (2 or 4, default 2)      16-column slabs per wave (64*nsub columns per workgroup)
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
- *   "attn_chunk"      (128 or 256, default 128) committed cache rows per attention workgroup
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)
+ *   "attn_chunk"      (128 or 256, default 128) committed cache rows per attention workgroup
  *   "attn_mfma"       (0 or 1, default 1)      0: plain attention kernel instead of the MFMA one     */
 int cerberus_set_param(cerberus_ctx *ctx, const char *name, int32_t value);
 
