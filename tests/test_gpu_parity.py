@@ -493,6 +493,53 @@ def test_tiny_odd_tree_shapes(tree):
     pair.engine.close()
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_tiny_random_launches(seed):
+    """Seeded random launches: tree shape, batch, prefix lengths (down to a single committed row),
+    which sequences take the one-token step, and per-sequence candidates planted to a random depth
+    on a random child rank, so that acceptance, compaction and packing meet in combinations the
+    hand-written cases do not list.  Three chained launches per case; every sequence is compared."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = F32 if seed % 5 == 4 else BF16
+    tree = ["tiny", "p63", f"rand{int(rng.integers(20, 60))}s{seed}k4", f"rand{int(rng.integers(66, 140))}s{seed}k4",
+            "chain4", "p63", "tiny", f"rand{int(rng.integers(2, 16))}s{seed}k4", "p63", "bfs3x40"][seed]
+    max_batch = int(rng.integers(1, 6))
+    batch = int(rng.integers(1, max_batch + 1))
+    pair = H.Pair("tiny", dtype, tree, seed=seed, max_batch=max_batch, kv_capacity=384, **({"topk": 6} if tree == "p63" else {}))
+    cfg = pair.cfg
+    Hc, K = cfg["n_cerb_heads"], cfg["topk"]
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    tol = H.TOL_BF16_TINY if dtype == BF16 else None
+    osts, greedy, done = [], [], []
+    for b in range(batch):
+        n_prompt = int(rng.choice([1, 2, 3, 17, 64, 127, 128, 129, 200])) if rng.random() < 0.6 else int(rng.integers(1, 230))
+        prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=500 + 10 * seed + b).numpy()
+        osts.append(orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity))
+        ref = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+        greedy.append(orc.greedy_decode(cfg, pair.W, ref["kv"], ref["L"], ref["root"], 3 * (Hc + 1) + 2))
+        done.append(0)
+    say(f"  seed {seed}: tree {tree} ({pair.T} nodes), dtype {dtype}, batch {batch}/{max_batch}, prefixes {[o['L'] for o in osts]}")
+    for step in range(3):
+        for b, ost in enumerate(osts):
+            cand = rng.integers(0, cfg["vocab"], size=(Hc, K))
+            for i in range(int(rng.integers(0, Hc + 1))):
+                cand[i, int(rng.integers(0, K))] = greedy[b][done[b] + 1 + i]
+            ost["cand"] = cand
+            ost["flag"] = int(rng.random() < 0.3)
+            H.round_oracle_kv(ost, dtype)
+            H.upload_sequence(st, b, ost, dtype)
+        outs = [pair.oracle_step(ost) for ost in osts]
+        pair.engine.verify_step(st, batch)
+        torch.cuda.synchronize()
+        assert int(st.status[0]) == 0
+        for b, (ost, out) in enumerate(zip(osts, outs)):
+            rep = H.compare_step(cfg, out, st, taps, b, pair.T, dtype, ost, tol=tol)
+            assert not rep.failures, f"seed {seed} step {step} seq {b} (T={out['T']}, L={out['L_before']}, a={out['accept_len']}): " + "; ".join(rep.failures)
+            done[b] += out["accept_len"]
+    pair.engine.close()
+
+
 @pytest.mark.parametrize("dtype,attn_mfma", [(F32, 0), (BF16, 1)])
 def test_tiny_head_dim_128_full_tree(dtype, attn_mfma):
     """The 7B/13B head size (128) and the 64-node tree at a width the oracle can afford for every
