@@ -185,6 +185,9 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  * them changes what is computed, only how the launches are shaped:
  *   "gemm_target_wgs" (1..65536, default 768)  workgroups a GEMM launch aims for when choosing split-K
  *   "gemm_max_split"  (1..16, default 8)       upper bound of the split-K factor
+ *   "gemm_wg_slots"   (0..65536, default 512)  workgroups resident at once (2 per CU x 256 CUs): a split that
+ *                                              fills >= 90 % of them in one round is preferred; 0 = off
+ *   "gemm_uneven_split" (0 or 1, default 0)    1: take the split the target gives even if it does not divide K
  *   "gemm_nsub"       (2 or 4, default 2)      16-column slabs per wave (64*nsub columns per workgroup)
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)

@@ -82,7 +82,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1, attn_chunk = 128;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1, attn_chunk = 128, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
   void* workspace = nullptr;
@@ -231,8 +231,15 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
 int choose_split(const cerberus_ctx* c, int total_tiles, int chunks, int rows_max) {
   const int cap = std::min(c->max_split, chunks);
   if (rows_max <= 64) {
+    // A launch that fits the chip in one round of resident workgroups (two 64-row workgroups per CU)
+    // and fills at least 90 % of it beats one and a half rounds of shorter workgroups: it writes
+    // fewer partials and has no half-empty second round (QKV at d = 4096: 480 workgroups with 5
+    // splits, 29.5 us, against 768 with 8 splits, 31.1 us).  The ranges need not divide the chunks.
+    const int one_round = c->wg_slots / total_tiles;
+    if (one_round >= 1 && one_round <= cap && total_tiles * one_round * 10 >= c->wg_slots * 9) return one_round;
     int S = std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
     S = std::min(S, cap);
+    if (c->uneven_split) return S;
     // an uneven split leaves some workgroups with less to do and costs a whole extra partial: take
     // the next lower split that divides the chunks, if there is one nearby
     for (int s2 = S; s2 * 5 >= S * 3 && s2 >= 1; --s2)
@@ -246,7 +253,6 @@ int choose_split(const cerberus_ctx* c, int total_tiles, int chunks, int rows_ma
   double best_cost = std::fabs(std::log(1.0 / ideal));
   for (int s2 = 2; s2 <= cap; ++s2) {
     const int cps = ceil_div(chunks, s2);
-    if (ceil_div(chunks, cps) != s2) continue;   // same ranges as a smaller count
     const double imbalance = (double)cps * s2 / chunks - 1.0;
     const double cost = std::fabs(std::log((double)s2 / ideal)) + 3.0 * imbalance;
     if (cost < best_cost) { best = s2; best_cost = cost; }
@@ -264,16 +270,16 @@ void split_plan(const cerberus_ctx* c, GemmBatch& g, int rows_max) {
   for (int p = 0; p < g.n_prob; ++p) {
     GemmProb& P = g.p[p];
     if (c->cfg.dtype == CERBERUS_F32) {
-      P.S = 1; P.kps = 0;
+      P.S = 1; P.kps = 0; P.rem = 0;
     } else {
       // unit of a split: one LDS chunk of the kernel, 4 k-steps (128 columns of K) with both activation
       // planes, 8 with one (K is padded to 256, so either divides it)
       const int unit = g.split ? 4 : 8;
       const int chunks = P.K / (32 * unit);
       const int S = g.fixed_s1 ? 1 : choose_split(c, total_tiles, chunks, rows_max);
-      const int cps = ceil_div(chunks, S);
-      P.S = ceil_div(chunks, cps);
-      P.kps = cps * unit;
+      P.S = S;                              // S <= chunks
+      P.kps = (chunks / S) * unit;          // as even as whole chunks allow: the first chunks % S splits take one more
+      P.rem = chunks % S;
     }
     P.out = out;
     out += (size_t)P.S * P.out_rows * P.N;
@@ -709,6 +715,14 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
   } else if (n == "attn_chunk") {
     if (value != 128 && value != 256) return fail(CERBERUS_ERR_ARG, "attn_chunk must be 128 or 256");
     ctx->attn_chunk = value;
+  } else if (n == "gemm_wg_slots") {
+    if (value < 0 || value > 65536) return fail(CERBERUS_ERR_ARG, "gemm_wg_slots out of 0..65536");
+    ctx->wg_slots = value;
+    build_plans(ctx);
+  } else if (n == "gemm_uneven_split") {
+    if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "gemm_uneven_split must be 0 or 1");
+    ctx->uneven_split = value;
+    build_plans(ctx);
   } else if (n == "gemm_target_wgs") {
     if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "gemm_target_wgs out of 1..65536");
     ctx->target_wgs = value;

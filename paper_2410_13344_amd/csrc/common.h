@@ -71,6 +71,7 @@ struct GemmProb {
   int out_rows;
   int S;          // split-K factor
   int kps;        // k-steps (of 32) per split, a multiple of the kernel's LDS chunk (4 with both activation planes, 8 with one)
+  int rem;        // the first `rem` splits take one LDS chunk more than kps (a split count that does not divide the chunks)
 };
 
 enum { GEMM_MAX_PROB = 8 };

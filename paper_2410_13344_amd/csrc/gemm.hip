@@ -84,8 +84,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   static_assert((2 * KSC) % kRing == 0 && (kRing % KSC == 0 || KSC % kRing == 0),
                 "ring slots must be compile-time constants: k-step (chunk parity * KSC + s) lives in slot of that index mod kRing");
   const int ksteps = P.K / 32;               // K is a multiple of 256
-  const int ks0 = split * P.kps;             // kps is a multiple of KSC
-  const int ks1 = min(ks0 + P.kps, ksteps);
+  const int ks0 = split * P.kps + min(split, P.rem) * KSC;   // kps is a multiple of KSC
+  const int ks1 = min(ks0 + P.kps + (split < P.rem ? KSC : 0), ksteps);
   const int nchunks = (ks1 - ks0) / KSC;
   if (nchunks <= 0) return;                  // uniform over the workgroup
 

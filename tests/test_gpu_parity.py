@@ -602,6 +602,7 @@ def test_graph_replay_equals_eager_launch(tiny_pairs):
 @pytest.mark.parametrize("params", [
     {"gemm_nsub": 4}, {"gemm_target_wgs": 64}, {"gemm_target_wgs": 4096, "gemm_max_split": 16}, {"gemm_max_split": 1},
     {"act_split": 0}, {"act_split": 0, "gemm_nsub": 4, "attn_mfma": 0}, {"attn_chunk": 256}, {"attn_chunk": 128},
+    {"gemm_wg_slots": 0}, {"gemm_wg_slots": 40}, {"gemm_uneven_split": 1, "gemm_target_wgs": 100, "gemm_wg_slots": 0},
 ])
 def test_tiny_tuning_knobs_do_not_change_results(params):
     """Every value of the tuning knobs selects another tiling, split or kernel instance of the same
