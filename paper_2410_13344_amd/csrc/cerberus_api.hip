@@ -231,12 +231,14 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
 int choose_split(const cerberus_ctx* c, int total_tiles, int chunks, int rows_max) {
   const int cap = std::min(c->max_split, chunks);
   if (rows_max <= 64) {
+    // resident workgroups: two per CU of the 32- and 64-row instances, three of the 16-row one
+    const int slots = rows_max <= 16 ? c->wg_slots * 3 / 2 : c->wg_slots;
     // A launch that fits the chip in one round of resident workgroups (two 64-row workgroups per CU)
     // and fills at least 90 % of it beats one and a half rounds of shorter workgroups: it writes
     // fewer partials and has no half-empty second round (QKV at d = 4096: 480 workgroups with 5
     // splits, 29.5 us, against 768 with 8 splits, 31.1 us).  The ranges need not divide the chunks.
-    const int one_round = c->wg_slots / total_tiles;
-    if (one_round >= 1 && one_round <= cap && total_tiles * one_round * 10 >= c->wg_slots * 9) return one_round;
+    const int one_round = slots / total_tiles;
+    if (one_round >= 1 && one_round <= cap && total_tiles * one_round * 10 >= slots * 9) return one_round;
     int S = std::max(1, (c->target_wgs + total_tiles / 2) / total_tiles);
     S = std::min(S, cap);
     if (c->uneven_split) return S;
@@ -351,7 +353,9 @@ int check_state(const cerberus_ctx* c, const cerberus_state* st, int batch) {
 int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, int rows_static, int rows_max,
              const int* skip_flags, int n_skip, hipStream_t s, GemmProb* launched = nullptr) {
   GemmBatch g = plan;
-  if (rows_max > 64) split_plan(c, g, rows_max);
+  // plans are made for 17..64 rows; other row counts run other kernel instances or several row
+  // blocks and get their own split (only where the caller takes the launched description back)
+  if (launched && (rows_max > 64 || rows_max <= 16)) split_plan(c, g, rows_max);
   if (launched) *launched = g.p[0];
   g.n_rows = n_rows;
   g.rows_static = rows_static;
@@ -683,7 +687,8 @@ int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* str
   auto run = [&](const GemmBatch& g) -> int {
     for (int p = 0; p < g.n_prob; ++p)
       total += ((double)g.p[p].N * g.p[p].K + (double)rows * g.p[p].K * (g.split && ctx->elem == 2 ? 2 : 1)) * ctx->elem;
-    return run_gemm(ctx, g, nullptr, rows, rows, nullptr, 0, s);
+    GemmProb launched;   // layer and LM-head launches choose their split by row count, as in a step
+    return run_gemm(ctx, g, nullptr, rows, rows, nullptr, 0, s, head_kind ? nullptr : &launched);
   };
   if (kind <= 3) {
     const std::vector<GemmBatch>& v = kind == 0 ? ctx->p_qkv : kind == 1 ? ctx->p_o : kind == 2 ? ctx->p_gu : ctx->p_down;
