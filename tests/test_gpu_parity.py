@@ -106,6 +106,59 @@ def test_tiny_medusa_heads_mode(tiny_pairs, dtype):
     assert sum(r.cand_checked for _, r in reps) > 0
 
 
+@pytest.mark.parametrize("shape", [
+    dict(special_block=0), dict(special_block=2), dict(special_block=3),           # the link at the first, a middle, the last block
+    dict(special_block=0, n_resblocks=1), dict(n_cerb_heads=1), dict(n_cerb_heads=8, special_block=2),
+    dict(n_resblocks=16, special_block=15),
+])
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_tiny_head_layouts(dtype, shape):
+    """Where the special Resblock sits decides which blocks of heads 1.. are 2d wide and at which
+    stage a head reads its neighbour (Section 4.1): every position, a single block, a single head,
+    the largest head count and block count the library takes."""
+    say(f"tiny steps, head layout {shape}, dtype={dtype}")
+    pair = H.Pair("tiny", dtype, "tiny" if shape.get("n_cerb_heads", 4) >= 4 else "chain1", seed=3, max_batch=1, kv_capacity=256, **shape)
+    reps = _run_forced_steps(pair, 2, "heads", 1)
+    assert sum(r.cand_checked for _, r in reps) > 0
+    pair.engine.close()
+
+
+@pytest.mark.parametrize("limit", ["vocab", "d_model"])
+def test_limit_shapes(limit):
+    """The largest vocabulary (65536: sixteen top-k slices, the full id range of the argmax) and the
+    largest model width (8192: both column groups of the one-workgroup-per-row kernels, eight blocks
+    per row in the residual kernel) the library accepts, bf16, MFMA attention."""
+    if limit == "vocab":
+        over = dict(vocab=65536)
+    else:
+        over = dict(d_model=8192, n_heads=64, head_dim=128, n_layers=1, d_ffn=1024, vocab=1024, n_cerb_heads=2,
+                    n_resblocks=1, special_block=0)
+    say(f"limit shape {over}")
+    pair = H.Pair("tiny", BF16, "tiny" if limit == "vocab" else "chain2", seed=5, max_batch=2, kv_capacity=256, **over)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    osts = []
+    for b, n_prompt in enumerate((70, 9)):
+        prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=90 + b).numpy()
+        osts.append(orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity))
+    for step in range(2):
+        for b, ost in enumerate(osts):
+            ost["flag"] = 0
+            H.round_oracle_kv(ost, BF16)
+            H.upload_sequence(st, b, ost, BF16)
+        outs = [pair.oracle_step(ost) for ost in osts]
+        pair.engine.verify_step(st, 2)
+        torch.cuda.synchronize()
+        assert int(st.status[0]) == 0
+        for b, (ost, out) in enumerate(zip(osts, outs)):
+            rep = H.compare_step(cfg, out, st, taps, b, pair.T, BF16, ost, tol=H.TOL_BF16)
+            say(f"  step {step} seq {b}: logit_err={rep.max_logit_err:.2e} head_err={rep.max_head_logit_err:.2e} "
+                f"argmax {rep.argmax_checked} cand {rep.cand_checked}")
+            assert not rep.failures, f"{limit} step {step} seq {b}: " + "; ".join(rep.failures)
+    pair.engine.close()
+
+
 @pytest.mark.parametrize("tree", ["p120", "p150"])
 @pytest.mark.parametrize("dtype,attn_mfma", [(F32, 0), (BF16, 0), (BF16, 1)])
 def test_tiny_large_trees(dtype, attn_mfma, tree):
