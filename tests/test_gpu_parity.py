@@ -465,6 +465,34 @@ def test_capacity_overflow_sets_status_and_skips(tiny_pairs):
     assert torch.equal(before, st.kv)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_tree_that_exactly_fills_the_cache(dtype):
+    """A capacity that is no multiple of the attention chunk (333 rows), and a prefix that leaves
+    room for exactly the 16 rows of the tree: the last cache row is written and read, nothing beyond."""
+    pair = H.Pair("tiny", dtype, "tiny", seed=2, max_batch=1, kv_capacity=333)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    prompt = synth.make_token_ids(333 - pair.T, cfg["vocab"], seed=33).numpy()
+    ost = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+    ost["flag"] = 0
+    H.round_oracle_kv(ost, dtype)
+    H.upload_sequence(st, 0, ost, dtype)
+    out = pair.oracle_step(ost)
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    rep = H.compare_step(cfg, out, st, taps, 0, pair.T, dtype, ost, tol=H.TOL_BF16_TINY if dtype == BF16 else None)
+    assert not rep.failures, "; ".join(rep.failures)
+    # one more row of prefix and the same tree no longer fits
+    st.kv_len[0] = 333 - pair.T + 1
+    st.gate_flag[0] = 0
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) & B.DEV_KV_OVERFLOW
+    pair.engine.close()
+
+
 def test_bad_arguments_are_rejected(tiny_pairs):
     pair = tiny_pairs(F32)
     st = pair.engine.new_state()
