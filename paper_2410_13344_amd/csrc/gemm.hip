@@ -50,7 +50,8 @@ constexpr int kLdsRow = 512;
 #ifndef CERB_KRING
 #define CERB_KRING 8
 #endif
-constexpr int kRing = CERB_KRING;  // k-steps of weights in flight per wave
+constexpr int kRingSplit = CERB_KRING;  // k-steps of weights in flight per wave (half as many in the one-plane instances:
+                                         // their 8-k-step chunks need the registers, else the 64-row one spills)
 
 __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
   if (g.skip_flags == nullptr) return false;
@@ -81,6 +82,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int split = local % P.S;
   const int ntile = local / P.S;
   constexpr int KSC = SPLIT ? 4 : 8;         // k-steps per LDS chunk
+  constexpr int kRing = SPLIT ? kRingSplit : kRingSplit / 2;
   static_assert((2 * KSC) % kRing == 0 && (kRing % KSC == 0 || KSC % kRing == 0),
                 "ring slots must be compile-time constants: k-step (chunk parity * KSC + s) lives in slot of that index mod kRing");
   const int ksteps = P.K / 32;               // K is a multiple of 256
