@@ -292,6 +292,21 @@ class Engine:
                stream=None):
         cerberus_decode(self.ctx, st.struct, batch, n_steps, out_tokens, out_count, stream)
 
+    def generate(self, st: DeviceState, prompts, n_steps: int, stream=None):
+        """Prompt phase for every sequence, then n_steps chained decoding steps (Algorithm 1 from its
+        first line to its last); returns the committed token ids of every sequence.  Only calls and
+        buffers: everything is computed by cerberus_prefill and cerberus_decode."""
+        batch = len(prompts)
+        st.kv_len[:batch] = 0
+        for b, p in enumerate(prompts):
+            self.prefill(st, batch, b, p.to(device="cuda", dtype=torch.int32), stream)
+        cap = n_steps * (self.cfg["n_cerb_heads"] + 1)
+        log = torch.full((batch, cap), -1, dtype=torch.int32, device="cuda")
+        count = torch.zeros(batch, dtype=torch.int32, device="cuda")
+        self.decode(st, batch, n_steps, log, count, stream)
+        torch.cuda.synchronize()
+        return [log[b, :int(count[b])].cpu().tolist() for b in range(batch)]
+
     def set_taps(self, taps: Optional[DeviceTaps]):
         self._taps = taps
         cerberus_set_taps(self.ctx, taps.struct if taps is not None else None)

@@ -267,6 +267,41 @@ def test_decode_chains_steps_on_the_device_and_logs_tokens(tiny_pairs, dtype):
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
+def test_generate_from_prompts_equals_greedy_decoding(dtype):
+    """End to end, nothing injected: prompt phase and chained steps on the device for two sequences,
+    against plain greedy auto-regressive decoding in the oracle (the method is lossless: whatever
+    the heads propose, the committed stream is the base model's greedy stream).  Compared up to the
+    first token whose top-2 margin in the oracle is within the tolerance."""
+    pair = H.Pair("tiny", dtype, "tiny", seed=4, max_batch=2, kv_capacity=256)
+    cfg = pair.cfg
+    tol = H.TOL_F32 if dtype == F32 else H.TOL_BF16_TINY
+    st = pair.engine.new_state()
+    prompts = [synth.make_token_ids(n, cfg["vocab"], seed=300 + n) for n in (45, 17)]
+    n_steps = 12
+    got = pair.engine.generate(st, prompts, n_steps)
+    assert int(st.status[0]) == 0
+    for b, p in enumerate(prompts):
+        ost = orc.prefill(cfg, pair.W, p.numpy(), capacity=pair.kv_capacity)
+        assert len(got[b]) >= n_steps and int(st.kv_len[b]) == len(p) + len(got[b])
+        L, t, n_ok = ost["L"], ost["root"], 0
+        for k in range(len(got[b])):
+            if got[b][k] != t:
+                break
+            _, logits = orc.decoder_rows(cfg, pair.W, np.array([t]), np.array([L]), np.ones((1, 1), bool), ost["kv"], L)
+            L += 1
+            n_ok += 1
+            srt = -np.sort(-logits[0])
+            if srt[0] - srt[1] <= 2 * tol.logits:      # the next token is not decided within the tolerance
+                say(f"  seq {b}: margin {srt[0] - srt[1]:.2e} after {n_ok} tokens: comparison ends here")
+                n_ok = len(got[b])
+                break
+            t = int(orc.argmax_lowest(logits[0]))
+        say(f"  seq {b}: {len(got[b])} tokens generated, greedy stream matched")
+        assert n_ok == len(got[b]), f"seq {b}: token {n_ok} is {got[b][n_ok]}, greedy decoding gives {t}"
+    pair.engine.close()
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
 def test_prefill_seeds_the_first_step(tiny_pairs, dtype):
     """Algorithm 1 lines 1-5: the prompt's causal forward from an empty cache, in passes of T rows
     (100 tokens = 6 full passes and one of 4), then LM head, gate and heads on the last position.
