@@ -104,7 +104,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--param", action="append", default=[], help="library tuning knob name=value")
     ap.add_argument("--prefill", type=int, default=0, metavar="N",
-                    help="time the prompt phase (cerberus_prefill) of N tokens from an empty cache; value is per pass of T rows")
+                    help="time the prompt phase (cerberus_prefill) of N tokens from an empty cache; value is per pass of "
+                         "up to CERBERUS_MAX_TREE rows")
     ap.add_argument("--decode", type=int, default=0, metavar="N",
                     help="time N chained steps per call (cerberus_decode: device-side gate, token log); value is per step")
     ap.add_argument("--tree", default=None, help="candidate tree: p63 (default, 64 nodes), p120 or p150 (top-10 per head)")
@@ -176,7 +177,7 @@ def main() -> int:
     per_call = max(args.decode, 1)
     if args.prefill:
         prompt_dev = synth.make_token_ids(args.prefill, cfg["vocab"], seed=4).cuda()
-        per_call = (args.prefill + T - 1) // T          # passes per call
+        per_call = (args.prefill + B.CERBERUS_MAX_TREE - 1) // B.CERBERUS_MAX_TREE          # passes per call
 
     def step():
         st.kv_len.copy_(L_dev)          # every repetition sees the configured prefix lengths ...

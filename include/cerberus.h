@@ -147,13 +147,13 @@ int cerberus_verify_step(cerberus_ctx *ctx, const cerberus_state *st, int32_t ba
 int cerberus_ar_step(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch, void *stream);
 
 /* Prompt phase of Algorithm 1 (lines 1-5) for sequence `seq` of the batch: a causal forward of
- * `n_tokens` prompt tokens (DEVICE int32) appended at cache rows kv_len.., in passes of up to n_nodes
- * rows (the candidate tree's row budget), then on the last position the LM head (-> root_token), the
+ * `n_tokens` prompt tokens (DEVICE int32) appended at cache rows kv_len.., in passes of up to
+ * CERBERUS_MAX_TREE rows (the result does not depend on the pass size), then on the last position the LM head (-> root_token), the
  * gate (-> gate_flag, entropy) and, where the gate says parallel, the heads (-> cand): the state a
  * first decoding step starts from.  kv_len[seq] advances by n_tokens; accept_len[seq] is set to 0;
  * the other sequences of the batch are not touched.  Tokens outside the vocabulary count as token 0
  * and set CERBERUS_DEV_BAD_TOKEN; a prompt that does not fit the cache sets CERBERUS_DEV_KV_OVERFLOW
- * and stops where it no longer fits.                                                            */
+ * and stops at the first pass that no longer fits.                                                          */
 int cerberus_prefill(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch, int32_t seq,
                      const int32_t *tokens, int32_t n_tokens, void *stream);
 

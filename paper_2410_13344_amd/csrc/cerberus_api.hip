@@ -80,7 +80,7 @@ struct cerberus_ctx {
   const void* lm_head = nullptr;
 
   size_t part_floats = 0;
-  int n_chunks_max = 0, R64 = 0;
+  int n_chunks_max = 0, R64 = 0, prompt_rows = 0;
   cerberus_taps taps{};
   int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1, attn_chunk = 128, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
@@ -137,9 +137,12 @@ void fill_dims(cerberus_ctx* c, const cerberus_config* cfg, const cerberus_tree*
   D.sb = cfg->special_block; D.dtype = cfg->dtype; D.Bmax = cfg->max_batch; D.cap = cfg->kv_capacity;
   D.topk = cfg->topk; D.T = t->n_nodes; D.eps = cfg->rms_eps; D.threshold = cfg->entropy_threshold;
   c->elem = cfg->dtype == CERBERUS_F32 ? 4 : 2;
-  c->R64 = (int)align_up((size_t)cfg->max_batch * t->n_nodes, 64);
+  // A prompt pass is a chain of up to prompt_rows rows of one sequence, whatever the tree's size: room
+  // for it in the row buffers, the row map and the attention partials.
+  c->prompt_rows = CERBERUS_MAX_TREE;
+  c->R64 = (int)align_up((size_t)std::max(cfg->max_batch * t->n_nodes, c->prompt_rows), 64);
   D.R64 = c->R64;
-  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128) + ceil_div(t->n_nodes, 64);  // committed-row chunks + tree chunks
+  c->n_chunks_max = ceil_div(cfg->kv_capacity, 128) + ceil_div(std::max(t->n_nodes, c->prompt_rows), 64);  // committed-row chunks + tree chunks
 }
 
 // Assigns every workspace pointer of the context; with base == nullptr it only measures.
@@ -147,19 +150,20 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   const Dims& D = c->D;
   const cerberus_config& cfg = c->cfg;
   Bump b{base, 0};
-  const int T = D.T, B = D.Bmax, Rmax = B * T, R64 = c->R64, d = D.d, el = c->elem;
+  const int T = D.T, B = D.Bmax, Rmax = std::max(B * T, c->prompt_rows), R64 = c->R64, d = D.d, el = c->elem;
+  const int P = c->prompt_rows;
   c->tree.T = T;
   c->tree.parent = b.take<int>(T);
   c->tree.rank = b.take<int>(T);
   c->tree.depth = b.take<int>(T);
   c->tree.aw = ceil_div(T, 64);
   c->tree.anc = b.take<unsigned long long>((size_t)T * c->tree.aw);
-  c->chain.T = T;
+  c->chain.T = P;
   c->chain.parent = c->tree.parent;   // not read in a prompt pass
   c->chain.rank = c->tree.rank;       // not read in a prompt pass
-  c->chain.depth = b.take<int>(T);
-  c->chain.aw = c->tree.aw;
-  c->chain.anc = b.take<unsigned long long>((size_t)T * c->tree.aw);
+  c->chain.depth = b.take<int>(P);
+  c->chain.aw = ceil_div(P, 64);
+  c->chain.anc = b.take<unsigned long long>((size_t)P * c->chain.aw);
   c->inv_freq = b.take<double>(D.dh / 2);
   c->rm.n_rows = b.take<int>(1);
   c->rm.seq_row0 = b.take<int>(B);
@@ -191,7 +195,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   const size_t nmax = (size_t)std::max(std::max(3 * d, 2 * D.F), D.V);
   c->part_floats = 16 * std::max((size_t)R64 * nmax, (size_t)16 * D.Hc * std::max((size_t)2 * d, (size_t)D.V));
   c->part = b.take<float>(c->part_floats);
-  const size_t slots = (size_t)B * D.nH * c->n_chunks_max * align_up((size_t)D.T, 64);
+  const size_t slots = (size_t)B * D.nH * c->n_chunks_max * align_up((size_t)std::max(D.T, P), 64);
   c->attn_po = b.take<float>(slots * D.dh);
   c->attn_ml = b.take<float>(slots * 2);
   for (int i = 0; i < 2; ++i) {
@@ -311,12 +315,12 @@ void build_plans(cerberus_ctx* c) {
   const int d = D.d, L = D.n_layers;
   c->p_qkv.resize(L); c->p_o.resize(L); c->p_gu.resize(L); c->p_down.resize(L);
   for (int l = 0; l < L; ++l) {
-    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, c->R64, false); }
-    { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wo[l], &N, &K, c->R64, false); }
-    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, c->R64, false); }
-    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, c->R64, false); }
+    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, 64, false); }
+    { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wo[l], &N, &K, 64, false); }
+    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, 64, false); }
+    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, 64, false); }
   }
-  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, c->R64, false); }
+  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, 64, false); }
   c->p_res.resize(D.R);
   const void* A[CERBERUS_MAX_HEADS]; const void* W[CERBERUS_MAX_HEADS];
   int lda[CERBERUS_MAX_HEADS], N[CERBERUS_MAX_HEADS], K[CERBERUS_MAX_HEADS];
@@ -355,7 +359,10 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
   GemmBatch g = plan;
   // plans are made for 17..64 rows; other row counts run other kernel instances or several row
   // blocks and get their own split (only where the caller takes the launched description back)
-  if (launched && (rows_max > 64 || rows_max <= 16)) split_plan(c, g, rows_max);
+  if (launched && (rows_max > 64 || rows_max <= 16)) {
+    for (int p = 0; p < g.n_prob; ++p) g.p[p].out_rows = (int)align_up((size_t)rows_max, 64);   // partials packed for this launch
+    split_plan(c, g, rows_max);
+  }
   if (launched) *launched = g.p[0];
   g.n_rows = n_rows;
   g.rows_static = rows_static;
@@ -392,7 +399,7 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
                            c->ssq, rows_max, s));
     AttnArgs aa{};
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
-    aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)D.T, 64); aa.tc_max = ceil_div(D.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = D.T;
+    aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)tr.T, 64); aa.tc_max = ceil_div(tr.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = tr.T;
     aa.chunk = c->attn_chunk; aa.n_chunks_max = ceil_div(D.cap, c->attn_chunk) + aa.tc_max;   // <= c->n_chunks_max, which sized the partial buffers
     aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
@@ -461,7 +468,7 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
   return run_heads(c, st, batch, s);
 }
 
-// Prompt phase for one sequence: passes of up to T rows, each a chain (causal mask, positions
+// Prompt phase for one sequence: passes of up to prompt_rows rows, each a chain (causal mask, positions
 // L, L+1, ...) whose K/V rows land where they stay.
 int run_prompt(cerberus_ctx* c, const cerberus_state* st, int batch, int seq, const int* tokens, int n_tokens, hipStream_t s) {
   const Dims& D = c->D;
@@ -473,8 +480,8 @@ int run_prompt(cerberus_ctx* c, const cerberus_state* st, int batch, int seq, co
   } restore{c->taps, c->taps};
   c->taps.forced_node_argmax = nullptr;
   c->taps.forced_gate_hidden = nullptr;
-  for (int off = 0; off < n_tokens; off += D.T) {
-    const int n = std::min(D.T, n_tokens - off);
+  for (int off = 0; off < n_tokens; off += c->chain.T) {
+    const int n = std::min(c->chain.T, n_tokens - off);
     const bool last = off + n >= n_tokens;
     HIP_TRY(launch_assemble(D, c->chain, rm, *st, c->taps, batch, ASSEMBLE_PROMPT, PromptArgs{tokens + off, n, seq}, s));
     TRY(forward_rows(c, st, batch, n, c->chain, last, s));
@@ -564,13 +571,14 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   HIP_INIT(hipMemcpy((void*)c->tree.anc, c->anc.data(), c->anc.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy(c->inv_freq, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice));
   {
-    std::vector<int> cd(T);
-    std::vector<unsigned long long> ca((size_t)T * aw, 0ull);
-    for (int n = 0; n < T; ++n) {
+    const int P = c->chain.T, caw = c->chain.aw;
+    std::vector<int> cd(P);
+    std::vector<unsigned long long> ca((size_t)P * caw, 0ull);
+    for (int n = 0; n < P; ++n) {
       cd[n] = n;
-      for (int m = 0; m <= n; ++m) ca[(size_t)n * aw + (m >> 6)] |= 1ull << (m & 63);
+      for (int m = 0; m <= n; ++m) ca[(size_t)n * caw + (m >> 6)] |= 1ull << (m & 63);
     }
-    HIP_INIT(hipMemcpy((void*)c->chain.depth, cd.data(), T * sizeof(int), hipMemcpyHostToDevice));
+    HIP_INIT(hipMemcpy((void*)c->chain.depth, cd.data(), P * sizeof(int), hipMemcpyHostToDevice));
     HIP_INIT(hipMemcpy((void*)c->chain.anc, ca.data(), ca.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
   }
 

@@ -136,7 +136,7 @@ __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr,
         else tok = node == 0 ? st.root_token[b] : st.cand[(b * D.Hc + dep - 1) * D.topk + tr.rank[node]];
         if (tok < 0 || tok >= D.V) { atomicOr(st.status, (int)CERBERUS_DEV_BAD_TOKEN); tok = 0; }
         rm.row_tok[r] = tok;
-        if (tp.node_token) tp.node_token[b * tr.T + node] = tok;
+        if (tp.node_token && node < D.T) tp.node_token[b * D.T + node] = tok;   // the taps hold T rows per sequence
       }
     }
   }
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(1024) void k_add_rmsnorm(float* __restrict__ x, con
   }
   ss = block_sum(ss, sh);
   const float sc = 1.0f / sqrtf(ss / (float)d + eps);
-  float* tp = tap ? tap + ((size_t)rm.row_seq[r] * T_tree + rm.row_node[r]) * d : nullptr;
+  float* tp = (tap && rm.row_node[r] < T_tree) ? tap + ((size_t)rm.row_seq[r] * T_tree + rm.row_node[r]) * d : nullptr;   // T rows per sequence
 #pragma unroll
   for (int it = 0; it < 2; ++it) {
     const int c = (it * 1024 + threadIdx.x) * 4;
@@ -430,6 +430,7 @@ __global__ __launch_bounds__(1024) void k_row_argmax(const float* __restrict__ p
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
   const size_t slot = (size_t)rm.row_seq[r] * T_tree + rm.row_node[r];
+  const bool tapped = rm.row_node[r] < T_tree;   // the taps hold T rows per sequence; a prompt pass can be longer
   float bv = -INFINITY;
   int bi = INT_MAX;
   for (int v = threadIdx.x * 4; v < V; v += 4096) {   // V % 16 == 0
@@ -438,14 +439,14 @@ __global__ __launch_bounds__(1024) void k_row_argmax(const float* __restrict__ p
       const float4 p = *reinterpret_cast<const float4*>(part + s * pstride + (size_t)r * V + v);
       val.x += p.x; val.y += p.y; val.z += p.z; val.w += p.w;
     }
-    if (tp.logits) *reinterpret_cast<float4*>(tp.logits + slot * V + v) = val;
+    if (tp.logits && tapped) *reinterpret_cast<float4*>(tp.logits + slot * V + v) = val;
     better(bv, bi, val.x, v); better(bv, bi, val.y, v + 1); better(bv, bi, val.z, v + 2); better(bv, bi, val.w, v + 3);
   }
   block_argmax(bv, bi, shv, shi);
   if (threadIdx.x == 0) {
     int best = bi == INT_MAX ? 0 : bi;
-    if (tp.node_argmax) tp.node_argmax[slot] = best;
-    if (tp.forced_node_argmax) best = tp.forced_node_argmax[slot];
+    if (tp.node_argmax && tapped) tp.node_argmax[slot] = best;
+    if (tp.forced_node_argmax && tapped) best = tp.forced_node_argmax[slot];
     g[r] = best;
   }
 }

@@ -301,14 +301,14 @@ def test_generate_from_prompts_equals_greedy_decoding(dtype):
     pair.engine.close()
 
 
+@pytest.mark.parametrize("n_prompt", [100, 230])
 @pytest.mark.parametrize("dtype", [F32, BF16])
-def test_prefill_seeds_the_first_step(tiny_pairs, dtype):
-    """Algorithm 1 lines 1-5: the prompt's causal forward from an empty cache, in passes of T rows
-    (100 tokens = 6 full passes and one of 4), then LM head, gate and heads on the last position.
+def test_prefill_seeds_the_first_step(tiny_pairs, dtype, n_prompt):
+    """Algorithm 1 lines 1-5: the prompt's causal forward from an empty cache, in passes of up to 192
+    rows (100 tokens: one pass; 230: a full pass and one of 38), then LM head, gate and heads on the last position.
     Compared with the oracle's one-shot causal prefill: every K/V row, the logits of the last pass,
     the pending token, entropy and flag, the candidates; then one decoding step taken from the seeded
     state on both sides."""
-    n_prompt = 100
     # bf16: the rows of earlier passes are read back from the bf16 cache while the oracle keeps them
     # in float64, so the bar is the general bf16 one, not the teacher-forced tiny-shape one
     tol = H.TOL_F32 if dtype == F32 else H.TOL_BF16
@@ -334,10 +334,12 @@ def test_prefill_seeds_the_first_step(tiny_pairs, dtype):
             got = st.kv[l, kvi, 0, :, :n_prompt].double().cpu().numpy()
             want = ost["kv"][l][kvi][:, :n_prompt]
             assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, float(np.max(np.abs(got - want))))
-    n_last = n_prompt % T or T                 # rows of the last pass: taps hold them at slots 0..n_last-1
-    err = float(np.max(np.abs(taps.logits[:n_last].double().cpu().numpy() - logits[-n_last:])))
-    herr = float(np.max(np.abs(taps.h_last[:n_last].double().cpu().numpy() - h_last[-n_last:])))
-    say(f"  prefill: last pass of {n_last} rows, logits err {err:.2e}, h_last err {herr:.2e}")
+    P = B.CERBERUS_MAX_TREE                    # rows of a full pass
+    n_last = n_prompt % P or P                 # rows of the last pass: the taps hold its first T rows at slots 0..
+    k, first = min(n_last, T), n_prompt - n_last
+    err = float(np.max(np.abs(taps.logits[:k].double().cpu().numpy() - logits[first:first + k])))
+    herr = float(np.max(np.abs(taps.h_last[:k].double().cpu().numpy() - h_last[first:first + k])))
+    say(f"  prefill: last pass of {n_last} rows, first {k} tapped, logits err {err:.2e}, h_last err {herr:.2e}")
     assert err <= tol.logits and herr <= tol.hidden
     srt = -np.sort(-logits[-1])
     if srt[0] - srt[1] > 2 * tol.logits:
@@ -373,7 +375,7 @@ def test_prefill_seeds_the_first_step(tiny_pairs, dtype):
     pair.engine.prefill(st3, 1, 0, prompt[:40].cuda())
     torch.cuda.synchronize()
     assert int(st3.status[0]) & B.CERBERUS_DEV_KV_OVERFLOW
-    assert int(st3.kv_len[0]) == pair.kv_capacity - 20 + 16      # one pass of 16 fitted, the second did not
+    assert int(st3.kv_len[0]) == pair.kv_capacity - 20           # the one pass of 40 rows did not fit: nothing committed
     with pytest.raises(RuntimeError):
         pair.engine.prefill(st3, 1, 1, prompt.cuda())             # sequence index out of range
 
