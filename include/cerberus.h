@@ -153,7 +153,7 @@ int cerberus_ar_step(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch,
  * first decoding step starts from.  kv_len[seq] advances by n_tokens; accept_len[seq] is set to 0;
  * the other sequences of the batch are not touched.  Tokens outside the vocabulary count as token 0
  * and set CERBERUS_DEV_BAD_TOKEN; a prompt that does not fit the cache sets CERBERUS_DEV_KV_OVERFLOW
- * and stops at the first pass that no longer fits.                                                          */
+ * and stops at the first pass that no longer fits.                                             */
 int cerberus_prefill(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch, int32_t seq,
                      const int32_t *tokens, int32_t n_tokens, void *stream);
 
