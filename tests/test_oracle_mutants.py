@@ -81,6 +81,19 @@ MUTANTS = [
     ("prefill: gate on the first position", 'S, flag = gate(h_last[-1], cfg["entropy_threshold"])', 'S, flag = gate(h_last[0], cfg["entropy_threshold"])'),
     ("prefill: heads on the first position", 'cerberus_heads(cfg, W["heads"], h_last[-1])])', 'cerberus_heads(cfg, W["heads"], h_last[0])])'),
     ("greedy reference: position not advanced", "        L += 1\n", "        L += 0\n"),
+    ("rope: positions off by one", "ang = _f(pos)[:, None] *", "ang = (_f(pos)[:, None] + 1.0) *"),
+    ("rope: q rotated, k rotated the other way", 'k = probe("k", l, rope(qkv[:, d:2 * d].reshape(rows, nH, dh), pos, theta))', 'k = probe("k", l, rope(qkv[:, d:2 * d].reshape(rows, nH, dh), -np.asarray(pos), theta))'),
+    ("attention: softmax over the queries", "s = s - np.max(s, axis=1, keepdims=True)\n            e = np.exp(s)\n            p = probe(\"p\", l, e / np.sum(e, axis=1, keepdims=True))", "s = s - np.max(s)\n            e = np.exp(s)\n            p = probe(\"p\", l, e / np.sum(e, axis=0, keepdims=True))"),
+    ("attention: values of head 0 for every head", "o[:, h, :] = p @ V[h, :L + rows, :]", "o[:, h, :] = p @ V[0, :L + rows, :]"),
+    ("attention: output heads in reverse order", "x = x + o.reshape(rows, d) @", "x = x + o[:, ::-1, :].reshape(rows, d) @"),
+    ("embedding: row of the next token id", 'x = _f(W["embed"][np.asarray(tok, dtype=np.int64)])', 'x = _f(W["embed"][(np.asarray(tok, dtype=np.int64) + 1) % len(W["embed"])])'),
+    ("decoder: layers in reverse order", "lw = layers[l]", "lw = layers[cfg[\"n_layers\"] - 1 - l]"),
+    ("decoder: K/V of layer 0 for every layer", "K, V = kv[l]", "K, V = kv[0]"),
+    ("compaction: K and V swapped", "K[:, L + j, :] = K[:, L + path[j], :]\n            V[:, L + j, :] = V[:, L + path[j], :]", "K[:, L + j, :] = V[:, L + path[j], :]\n            V[:, L + j, :] = K[:, L + path[j], :]"),
+    ("compaction: only the first layer", "    for K, V in kv:\n        for j in range(1, len(path)):", "    for K, V in kv[:1]:\n        for j in range(1, len(path)):"),
+    ("step: committed tokens exclude the root", "committed = tok[path]", "committed = tok[path[1:]]"),
+    ("heads: every head gets head 0's blocks", 'blk = heads[i]["blocks"][s]', 'blk = heads[i if s == sb else 0]["blocks"][s] if len(heads[0]["blocks"][s]["b"]) == len(heads[i]["blocks"][s]["b"]) else heads[i]["blocks"][s]'),
+    ("top-k: k+1 entries", "return order[:k].astype(np.int64)", "return order[:k + 1].astype(np.int64)"),
     ("prefill: root from the first position", "root = int(argmax_lowest(logits[-1]))", "root = int(argmax_lowest(logits[0]))"),
     ("prefill: full visibility instead of causal", "vis = np.tril(np.ones((n, n), dtype=bool))", "vis = np.ones((n, n), dtype=bool)"),
 ]
