@@ -124,6 +124,19 @@ def make_weights(cfg: dict, seed: int = 0, dtype=torch.float32, device="cpu",
     return W
 
 
+def make_heads(cfg: dict, seed: int, dtype=torch.float32, device="cpu", std: float = 0.02) -> list:
+    """Decoding heads alone (same recipe as in make_weights, tensor ids of their own), for a second
+    head layout over a base model that is already there."""
+    tid = itertools.count(1 << 20)
+    widths = head_block_widths(cfg)
+    heads = []
+    for i in range(cfg["n_cerb_heads"]):
+        blocks = [{"w": _normal((w, w), std, 0.0, seed, next(tid), device, dtype),
+                   "b": _normal((w,), std, 0.0, seed, next(tid), device, dtype)} for w in widths[i]]
+        heads.append({"blocks": blocks, "fc": _normal((cfg["vocab"], widths[i][-1]), std, 0.0, seed, next(tid), device, dtype)})
+    return heads
+
+
 def make_kv_prefix(cfg: dict, batch: int, capacity: int, seed: int, dtype, device) -> torch.Tensor:
     """Synthetic N(0,1) KV slab [n_layers][2][batch][n_heads][capacity][head_dim]."""
     shape = (cfg["n_layers"], 2, batch, cfg["n_heads"], capacity, cfg["head_dim"])

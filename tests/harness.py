@@ -25,11 +25,18 @@ class Tol:
 
 
 TOL_F32 = Tol(logits=5e-5, hidden=5e-5, entropy=1e-5, kv_atol=2e-5, kv_rtol=2e-5)
-# bf16 GPU vs float64 oracle: 2e-2 max-abs on logits is the bar of the benchmark spec
-TOL_BF16 = Tol(logits=2e-2, hidden=3e-2, entropy=3e-2, kv_atol=3e-2, kv_rtol=2e-2)
+# bf16 GPU vs float64 oracle.  logits: 2e-2 max-abs, the one bar the benchmark spec gives, applied
+# flat to the LM head's and to the decoding heads' logits.  hidden: h_last is what the LM-head
+# matrix multiplies (rows of norm ~0.02 * sqrt(d) ~ 1.3), so the same bar.  entropy: S is a smooth
+# function of h_last; the errors measured at the tiny, 7B and 13B shapes are at most 1e-5 bits, the bar
+# is 5e-4, and the gate flag is compared whenever |S - T| exceeds twice the bar = 1e-3 bits.  kv: a cache row
+# is one bf16 rounding (relative 2^-8 = 3.9e-3) of a value of magnitude up to ~6, plus the error of
+# the row before rounding, which can move the rounding by one step: two steps of 2^-8 relative
+# (kv_rtol 8e-3); the absolute floor covers values near zero (value error measured: 2e-4).
+TOL_BF16 = Tol(logits=2e-2, hidden=2e-2, entropy=5e-4, kv_atol=2e-3, kv_rtol=8e-3)
 # the two-layer tiny model amplifies nothing: with hi+lo bf16 GEMM inputs its logits sit within 2e-4
 # of the oracle, so the tiny-shape tests use a ten times tighter bar (more integer decisions checked)
-TOL_BF16_TINY = Tol(logits=2e-3, hidden=4e-3, entropy=2e-3, kv_atol=3e-2, kv_rtol=2e-2)
+TOL_BF16_TINY = Tol(logits=2e-3, hidden=4e-3, entropy=5e-4, kv_atol=2e-3, kv_rtol=8e-3)
 
 
 def torch_dtype(dtype: int):
@@ -63,11 +70,9 @@ def round_oracle_kv(ost: dict, dtype: int) -> None:
 
 
 def head_logit_tol(tol: Tol, want: np.ndarray) -> float:
-    """Tolerance on one decoding head's logits.  The LM-head bar is quoted for logits of unit
-    scale (rms 1.28 at the 7B shape); a head's logits are the same kind of product taken after
-    four Resblocks that each grow the state, so the input error arrives amplified by the same
-    factor as the logits themselves: the bar scales with their rms (never below the LM-head bar)."""
-    return tol.logits * max(1.0, float(np.sqrt(np.mean(np.square(want)))))
+    """Tolerance on one decoding head's logits: the same flat max-abs bar as the LM head's (the
+    task statement gives one bar for logits), whatever the scale of the head's logits."""
+    return tol.logits
 
 
 def _margin_ok(sorted_vals: np.ndarray, j: int, tol: float) -> bool:
@@ -160,7 +165,7 @@ def compare_step(cfg: dict, out: dict, st: B.DeviceState, taps: B.DeviceTaps, b:
         if not rep.entropy_err <= tol.entropy:
             bad(f"entropy {S_gpu} vs {out['entropy']}")
         thr = cfg["entropy_threshold"]
-        if abs(out["entropy"] - thr) > 2 * tol.entropy or np.isinf(thr):
+        if abs(out["entropy"] - thr) > max(1e-3, 2 * tol.entropy) or np.isinf(thr):
             rep.flag_checked = True
             if int(st.gate_flag[b]) != out["flag"]:
                 bad(f"gate flag {int(st.gate_flag[b])} vs {out['flag']} (S={out['entropy']}, T={thr})")
@@ -192,13 +197,17 @@ class Pair:
     """An oracle model and a device engine built from the same seeded weights."""
 
     def __init__(self, name: str, dtype: int, tree: str, seed: int = 0, max_batch: int = 1, kv_capacity: int = 256,
-                 lazy_host: bool = False, share: Optional["Pair"] = None, **overrides):
+                 lazy_host: bool = False, share: Optional["Pair"] = None, heads_seed: Optional[int] = None, **overrides):
         self.cfg = synth.make_config(name, **overrides)
         self.dtype = dtype
         self.parent, self.rank = synth.make_tree(tree, self.cfg["n_cerb_heads"])
         self.T = len(self.parent)
         if share is not None:                 # same seeded weights (device and host views), another engine
             self.W_dev, self.W = share.W_dev, share.W
+            if heads_seed is not None:        # the shared base model under decoding heads of another layout
+                heads = synth.make_heads(self.cfg, heads_seed, dtype=torch_dtype(dtype), device="cuda")
+                self.W_dev = dict(share.W_dev, heads=heads)
+                self.W = dict(share.W, heads=synth.to_host_f32(heads))
         else:
             self.W_dev = synth.make_weights(self.cfg, seed=seed, dtype=torch_dtype(dtype), device="cuda")
             self.W = synth.to_host_lazy(self.W_dev) if lazy_host else synth.to_host_f32(self.W_dev)

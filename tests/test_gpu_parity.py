@@ -776,10 +776,10 @@ def test_tiny_maximum_batch_and_tree():
 
 
 # ---------------------------------------------------------------------------------------------
-# full size: the 7B shape in the launch configuration bench.py times (bf16, 64-node tree, prefix
-# 1024).  The oracle cannot afford all 64 nodes, so it runs one sampled root-to-leaf path as a chain
-# tree: a node's result depends only on the prefix and its ancestors, so the chain's rows must equal
-# the corresponding rows of the full tree pass.
+# full size: the 7B and 13B shapes in the launch configurations bench.py times (bf16, prefix 1024 /
+# 2048).  The oracle runs the WHOLE candidate tree (a 64-node 7B step takes it a few seconds), so
+# every row's logits, hidden state and argmax, the forced depth-4 acceptance and its compaction in
+# every layer, the gate, all heads' logits and the candidates are compared.
 # ---------------------------------------------------------------------------------------------
 @pytest.fixture(scope="module")
 def pair_7b():
@@ -787,17 +787,25 @@ def pair_7b():
     return H.Pair("7b", BF16, "p63", seed=0, max_batch=1, kv_capacity=1280, lazy_host=True)
 
 
-def test_7b_full_size_sampled_path_matches_oracle(pair_7b):
-    _full_size_sampled_path(pair_7b, 1024, 1280)
+def test_7b_full_size_whole_tree_matches_oracle(pair_7b):
+    _full_size_step(pair_7b, 1024, 1280)
 
 
-def test_7b_120_path_tree_sampled_path_matches_oracle(pair_7b):
+def test_7b_120_path_tree_whole_tree_matches_oracle(pair_7b):
     """The tree size of the paper's main table (Section 5.1: 120 paths, top-10 per head): 121 nodes,
     so two 64-row blocks in every GEMM, two query blocks and two tree chunks in attention, two mask
-    words per node.  The sampled chain ends in the last node, so it crosses both blocks."""
+    words per node."""
     pair = H.Pair("7b", BF16, "p120", max_batch=1, kv_capacity=1280, share=pair_7b, topk=10)
     assert pair.T == 121 and max(pair.rank) < 10
-    _full_size_sampled_path(pair, 1024, 1280)
+    _full_size_step(pair, 1024, 1280)
+    pair.engine.close()
+
+
+def test_7b_150_path_tree_whole_tree_matches_oracle(pair_7b):
+    """The largest tree of Section 5.1 (150 paths): 151 nodes, three row blocks, three mask words."""
+    pair = H.Pair("7b", BF16, "p150", max_batch=1, kv_capacity=1280, share=pair_7b, topk=10)
+    assert pair.T == 151
+    _full_size_step(pair, 1024, 1280)
     pair.engine.close()
 
 
@@ -829,17 +837,56 @@ def test_7b_step_is_bitwise_reproducible(pair_7b):
     assert int(st.status[0]) == 0
 
 
-def test_13b_full_size_sampled_path_matches_oracle():
+def test_7b_ar_step_reached_through_the_gate_matches_oracle(pair_7b):
+    """A sequence whose gate flag says auto-regressive, run by cerberus_verify_step: the launches are
+    sized for the whole tree but carry one row (the kernels' paths for partly filled row tiles).
+    Nothing forced: logits, argmax, committed token, cache row, gate and the heads' candidates for the
+    next step against the oracle's one-row step."""
+    pair = pair_7b
+    cfg, cap, L, tol = pair.cfg, pair.kv_capacity, 1024, H.TOL_BF16
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
+    root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    cand = synth.make_candidates(cfg, 1, seed=3)[0]
+    st.kv_len[0], st.root_token[0], st.gate_flag[0] = L, root, 1
+    st.cand[0] = cand.cuda()
+    kv_host = [(st.kv[l, 0, 0].double().cpu().numpy(), st.kv[l, 1, 0].double().cpu().numpy()) for l in range(cfg["n_layers"])]
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    ost = orc.new_state(kv_host, L, root, cand.numpy(), 1)
+    out = orc.verify_step(cfg, pair.W, pair.parent, pair.rank, ost)
+    assert out["T"] == 1
+    rep = H.compare_step(cfg, out, st, taps, 0, pair.T, BF16, ost, tol=tol)
+    say(f"7B AR step through the gate: logits err {rep.max_logit_err:.3e}, h_last err {rep.max_hidden_err:.3e}, "
+        f"head logits err {rep.max_head_logit_err:.3e}, entropy err {rep.entropy_err:.2e}, candidates {rep.cand_checked} checked")
+    assert not rep.failures, "; ".join(rep.failures)
+    assert rep.accept_checked and rep.flag_checked and rep.cand_checked > 0
+
+
+def test_13b_full_size_whole_tree_matches_oracle():
     """configs[3]: 40 layers, d 5120, 40 heads, FFN 13824, five decoding heads, prefix 2048."""
     say("13B: building weights and engine")
     pair = H.Pair("13b", BF16, "p63", seed=0, max_batch=1, kv_capacity=2304, lazy_host=True)
-    _full_size_sampled_path(pair, 2048, 2304)
+    _full_size_step(pair, 2048, 2304)
     pair.engine.close()
 
 
-def _full_size_sampled_path(pair, L, cap):
+def _deepest_path(pair):
+    """Root-to-leaf node list ending in the deepest leaf with the largest index."""
+    depth, _ = orc.tree_tables(pair.parent)
+    leaf = max(n for n in range(pair.T) if depth[n] == max(depth))
+    nodes = []
+    n = leaf
+    while n >= 0:
+        nodes.append(n)
+        n = pair.parent[n]
+    return nodes[::-1]
+
+
+def _full_size_step(pair, L, cap):
     cfg, T, tol = pair.cfg, pair.T, H.TOL_BF16
-    tag = f"{cfg['n_layers']}x{cfg['d_model']}"
+    tag = f"{cfg['n_layers']}x{cfg['d_model']} T={T}"
     st = pair.engine.new_state()
     st.kv.copy_(synth.make_kv_prefix(cfg, 1, cap, seed=0, dtype=torch.bfloat16, device="cuda"))
     root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
@@ -847,90 +894,185 @@ def _full_size_sampled_path(pair, L, cap):
     st.kv_len[0], st.root_token[0], st.gate_flag[0] = L, root, 0
     st.cand[0] = cand.cuda()
 
-    # sampled path: the deepest leaf with the largest index
-    depth, _ = orc.tree_tables(pair.parent)
-    leaf = max(n for n in range(T) if depth[n] == cfg["n_cerb_heads"])
-    nodes = []
-    n = leaf
-    while n >= 0:
-        nodes.append(n)
-        n = pair.parent[n]
-    nodes.reverse()
-    chain_parent = [-1] + list(range(len(nodes) - 1))
-    chain_rank = [pair.rank[n] for n in nodes]
-
-    # force the acceptance down that path on both sides, so that a depth-4 commit and its
-    # compaction are exercised at full size; 777 is the (forced) next root
+    # force the acceptance down the deepest path on both sides (random-init heads never get a
+    # candidate accepted), so that a full-depth commit and its compaction are exercised at full
+    # size; 777 is the (forced) next root, -1 (no token) everywhere off the path
+    nodes = _deepest_path(pair)
     taps = pair.taps(forced_argmax=True)
-    forced_full = torch.full((T,), -1, dtype=torch.int32)
     tok_full = orc.tree_tokens(root, cand.numpy(), pair.parent, pair.rank)
-    forced_chain = np.zeros(len(nodes), dtype=np.int64)
+    forced = np.full(T, -1, dtype=np.int64)
     for j, n in enumerate(nodes):
-        nxt = tok_full[nodes[j + 1]] if j + 1 < len(nodes) else 777
-        forced_full[n] = int(nxt)
-        forced_chain[j] = int(nxt)
-    taps.forced_node_argmax.copy_(forced_full.cuda())
+        forced[n] = int(tok_full[nodes[j + 1]]) if j + 1 < len(nodes) else 777
+    taps.forced_node_argmax.copy_(torch.from_numpy(forced).to(torch.int32).cuda())
 
     kv_before = st.kv.clone()
     pair.engine.verify_step(st, 1)
     torch.cuda.synchronize()
     assert int(st.status[0]) == 0
-    say(tag + ": device step done; running the oracle on the sampled chain " + str(nodes))
+    say(tag + ": device step done; running the oracle on the whole tree")
 
     kv_host = [(kv_before[l, 0, 0].double().cpu().numpy(), kv_before[l, 1, 0].double().cpu().numpy())
                for l in range(cfg["n_layers"])]
     W_lazy = pair.W
-    W_lazy["layers"]._on_access = lambda l: say(f"  oracle layer {l}") if l % 4 == 0 else None
+    W_lazy["layers"]._on_access = lambda l: say(f"  oracle layer {l}") if l % 8 == 0 else None
     ost = orc.new_state(kv_host, L, root, cand.numpy(), 0)
-    out = orc.verify_step(cfg, W_lazy, chain_parent, chain_rank, ost, forced_node_argmax=forced_chain)
-    assert out["path"] == list(range(len(nodes))) and out["accept_len"] == len(nodes)
+    out = orc.verify_step(cfg, W_lazy, pair.parent, pair.rank, ost, forced_node_argmax=forced)
+    assert out["T"] == T and out["path"] == nodes
 
-    idx = torch.tensor(nodes)
-    assert np.array_equal(taps.node_token[idx].cpu().numpy(), out["tok"])
-    logits = taps.logits[idx].double().cpu().numpy()
-    err = float(np.max(np.abs(logits - out["logits"])))
-    herr = float(np.max(np.abs(taps.h_last[idx].double().cpu().numpy() - out["h_last"])))
-    say(f"{tag}: logits max-abs err {err:.3e} (std of logits {out['logits'].std():.3f}), h_last err {herr:.3e}")
-    assert err <= tol.logits
-    srt = -np.sort(-out["logits"], axis=1)
-    safe = (srt[:, 0] - srt[:, 1]) > 2 * tol.logits
-    g_real = np.argmax(out["logits"], axis=1)
-    assert np.array_equal(taps.node_argmax[idx].cpu().numpy()[safe], g_real[safe])
-    say(f"{tag}: argmax checked on {int(safe.sum())}/{len(nodes)} nodes")
+    rep = H.compare_step(cfg, out, st, taps, 0, T, BF16, ost, forced_argmax=True, tol=tol)
+    say(f"{tag}: all {T} rows: logits max-abs err {rep.max_logit_err:.3e} (std of logits {out['logits'].std():.3f}), h_last err "
+        f"{rep.max_hidden_err:.3e}, real argmax checked {rep.argmax_checked}/{T}, entropy err {rep.entropy_err:.2e}, head logits err "
+        f"{rep.max_head_logit_err:.3e}, candidates checked {rep.cand_checked}/{rep.cand_checked + rep.cand_skipped}")
+    assert not rep.failures, "; ".join(rep.failures)
+    assert rep.accept_checked and rep.flag_checked and rep.cand_checked > 0 and rep.argmax_checked > T // 2
+    assert int(st.accept_len[0]) == len(nodes) and int(st.root_token[0]) == 777
+    assert torch.equal(st.kv[:, :, :, :, :L], kv_before[:, :, :, :, :L])       # committed rows untouched
 
-    a = int(st.accept_len[0])
-    assert a == len(nodes)
-    assert st.accepted_nodes[0, :a].cpu().tolist() == nodes
-    assert st.accepted_tokens[0, :a].cpu().tolist() == [int(t) for t in out["committed"]]
-    assert int(st.root_token[0]) == 777 and int(st.kv_len[0]) == L + a
-    # compaction: rows L..L+a-1 now hold the accepted nodes' K/V (the oracle's chain wrote them there
-    # directly); the copy itself is checked bit for bit in test_accept_entry_point_is_bit_exact
-    for l in (0, 13, cfg["n_layers"] - 1):
+
+# ---------------------------------------------------------------------------------------------
+# The widened rows at full size: independent heads, the multi-step driver, the prompt phase.
+# ---------------------------------------------------------------------------------------------
+def test_7b_independent_heads_step_matches_oracle(pair_7b):
+    """special_block = -1 at the 7B shape: four d-wide heads over the shared base model.  The step
+    runs the whole tree; the acceptance is forced to stop at the root on both sides, so the oracle
+    needs the root's row only (a tree of size 1 gives the same row 0 as any tree pass) and then
+    runs its heads on that row's hidden state."""
+    pair = H.Pair("7b", BF16, "p63", max_batch=1, kv_capacity=1280, share=pair_7b, heads_seed=9, special_block=-1)
+    cfg, T, L, tol = pair.cfg, pair.T, 1024, H.TOL_BF16
+    assert all(w == cfg["d_model"] for ws in synth.head_block_widths(cfg) for w in ws)
+    st = pair.engine.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, 1, pair.kv_capacity, seed=0, dtype=torch.bfloat16, device="cuda"))
+    root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    cand = synth.make_candidates(cfg, 1, seed=3)[0]
+    st.kv_len[0], st.root_token[0], st.gate_flag[0] = L, root, 0
+    st.cand[0] = cand.cuda()
+    taps = pair.taps(forced_argmax=True)
+    forced = np.full(T, -1, dtype=np.int64)
+    forced[0] = 777                                   # no child carries it: the walk stops at the root
+    taps.forced_node_argmax.copy_(torch.from_numpy(forced).to(torch.int32).cuda())
+    kv_host = [(st.kv[l, 0, 0].double().cpu().numpy(), st.kv[l, 1, 0].double().cpu().numpy()) for l in range(cfg["n_layers"])]
+    pair.engine.verify_step(st, 1)
+    torch.cuda.synchronize()
+    ost = orc.new_state(kv_host, L, root, cand.numpy(), 0)
+    out = orc.verify_step(cfg, pair.W, [-1], [0], ost, forced_node_argmax=forced[:1])
+    rep = H.compare_step(cfg, out, st, taps, 0, T, BF16, ost, forced_argmax=True, tol=tol)
+    say(f"7B independent heads: logits err {rep.max_logit_err:.3e}, head logits err {rep.max_head_logit_err:.3e}, "
+        f"candidates checked {rep.cand_checked}/{rep.cand_checked + rep.cand_skipped}")
+    assert not rep.failures, "; ".join(rep.failures)
+    assert rep.accept_checked and rep.flag_checked and rep.cand_checked > 0
+    pair.engine.close()
+
+
+def test_7b_decode_two_chained_steps_match_oracle(pair_7b):
+    """cerberus_decode at the 7B shape, nothing forced: two steps enqueued in one call, the second
+    one drafted by the first one's heads.  The oracle runs the same two whole-tree steps; the token
+    log is compared up to the first decision whose margin is within the tolerance, and the second
+    step's rows (the taps hold the last step's) are compared like any single step."""
+    pair = pair_7b
+    cfg, T, L, tol = pair.cfg, pair.T, 1024, H.TOL_BF16
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    st.kv.copy_(synth.make_kv_prefix(cfg, 1, pair.kv_capacity, seed=0, dtype=torch.bfloat16, device="cuda"))
+    root = int(synth.make_token_ids(1, cfg["vocab"], seed=2)[0])
+    cand = synth.make_candidates(cfg, 1, seed=3)[0]
+    st.kv_len[0], st.root_token[0], st.gate_flag[0] = L, root, 0
+    st.cand[0] = cand.cuda()
+    kv_host = [(st.kv[l, 0, 0].double().cpu().numpy(), st.kv[l, 1, 0].double().cpu().numpy()) for l in range(cfg["n_layers"])]
+    log = torch.full((1, 16), -1, dtype=torch.int32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pair.engine.decode(st, 1, 2, log, count)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    got = log[0, :int(count[0])].cpu().tolist()
+    assert int(st.kv_len[0]) == L + len(got)
+
+    ost = orc.new_state(kv_host, L, root, cand.numpy(), 0)
+    want, clear = [], True
+    for step in range(2):
+        if step == 1:                                # the device's second step read bf16 cache rows
+            H.round_oracle_kv(ost, BF16)
+        out = orc.verify_step(cfg, pair.W, pair.parent, pair.rank, ost)
+        srt = -np.sort(-out["logits"][out["path"]], axis=1)
+        margin = float(np.min(srt[:, 0] - srt[:, 1]))
+        cmargin = min(float(np.min(-np.diff(-np.sort(-hl)[:cfg["topk"] + 1]))) for hl in out["head_logits"])
+        say(f"  7B decode step {step}: accept {out['accept_len']}, argmax margin {margin:.2e}, candidate margin {cmargin:.2e}")
+        if margin <= 2 * tol.logits or (step == 0 and cmargin <= 2 * tol.logits):
+            clear = False
+            break
+        want += [int(t) for t in out["committed"]]
+    assert got[:len(want)] == want and len(want) >= 1
+    if clear:
+        assert len(got) == len(want)
+        rep = H.compare_step(cfg, out, st, taps, 0, T, BF16, ost, tol=tol)
+        say(f"  7B decode, second step: logits err {rep.max_logit_err:.3e}, head logits err {rep.max_head_logit_err:.3e}")
+        assert not rep.failures, "; ".join(rep.failures)
+    else:
+        say("  7B decode: a decision of the first step sits within the tolerance; compared the log up to it")
+
+
+def test_7b_prefill_two_passes_matches_oracle(pair_7b):
+    """cerberus_prefill at the 7B shape: 230 prompt tokens from an empty cache (a pass of 192 rows and
+    one of 38), against the oracle's one-shot causal prefill: cache rows, the last pass's logits and
+    hidden states, pending token, gate, the heads' logits and candidates."""
+    pair = pair_7b
+    cfg, T, tol, n_prompt = pair.cfg, pair.T, H.TOL_BF16, 230
+    taps = pair.taps()
+    prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=21)
+    st = pair.engine.new_state()
+    st.kv_len[0] = 0
+    st.gate_flag[0] = 1
+    pair.engine.prefill(st, 1, 0, prompt.cuda())
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0 and int(st.kv_len[0]) == n_prompt
+    # The oracle takes the same two passes, its cache rounded to bf16 between them: the device's
+    # second pass reads the first pass's rows from the bf16 cache, and the storage type of the cache
+    # is part of the configuration, not an error of the path (that passes and a one-shot forward
+    # agree is pinned on the oracle itself).
+    say("7B prefill: device done; oracle's causal forward over 192 + 38 rows")
+    P = B.CERBERUS_MAX_TREE
+    ost = {"kv": orc.new_kv(cfg, n_prompt)}
+    kv = ost["kv"]
+    hs, ls = [], []
+    for off in range(0, n_prompt, P):
+        n = min(P, n_prompt - off)
+        h_p, l_p = orc.decoder_rows(cfg, pair.W, prompt.numpy()[off:off + n], np.arange(off, off + n),
+                                    np.tril(np.ones((n, n), dtype=bool)), kv, off)
+        hs.append(h_p)
+        ls.append(l_p)
+        if off + n < n_prompt:
+            H.round_oracle_kv(ost, BF16)
+            kv = ost["kv"]
+    h_last, logits = np.concatenate(hs), np.concatenate(ls)
+    for l in (0, cfg["n_layers"] // 2, cfg["n_layers"] - 1):
         for kvi in (0, 1):
-            got = st.kv[l, kvi, 0, :, L:L + a].double().cpu().numpy()
-            want = ost["kv"][l][kvi][:, L:L + a]
-            assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, np.max(np.abs(got - want)))
-    assert torch.equal(st.kv[:, :, :, :, :L], kv_before[:, :, :, :, :L])
-
-    S_gpu = float(st.entropy[0])
-    say(f"{tag}: entropy {S_gpu:.5f} vs {out['entropy']:.5f}")
-    assert abs(S_gpu - out["entropy"]) <= tol.entropy and int(st.gate_flag[0]) == 0
+            got = st.kv[l, kvi, 0, :, :n_prompt].double().cpu().numpy()
+            want = kv[l][kvi][:, :n_prompt]
+            assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, float(np.max(np.abs(got - want))))
+    n_last = n_prompt % P or P
+    k, first = min(n_last, T), n_prompt - n_last
+    err = float(np.max(np.abs(taps.logits[:k].double().cpu().numpy() - logits[first:first + k])))
+    herr = float(np.max(np.abs(taps.h_last[:k].double().cpu().numpy() - h_last[first:first + k])))
+    say(f"7B prefill: last pass of {n_last} rows, {k} tapped: logits err {err:.3e}, h_last err {herr:.3e}")
+    assert err <= tol.logits and herr <= tol.hidden
+    srt = -np.sort(-logits[-1])
+    if srt[0] - srt[1] > 2 * tol.logits:
+        assert int(st.root_token[0]) == int(orc.argmax_lowest(logits[-1]))
+    S, flag = orc.gate(h_last[-1], cfg["entropy_threshold"])
+    assert abs(float(st.entropy[0]) - S) <= tol.entropy and int(st.gate_flag[0]) == flag == 0
+    want_hl = np.stack(orc.cerberus_heads(cfg, pair.W["heads"], h_last[-1]))
     hl = taps.head_logits[0].double().cpu().numpy()
-    want = np.stack(out["head_logits"])
-    herr2 = float(np.max(np.abs(hl - want)))
-    say(f"{tag}: head logits max-abs err {herr2:.3e} (std {want.std():.3f})")
-    K = cfg["topk"]
-    cand_gpu = st.cand[0].cpu().numpy()
+    herr2 = float(np.max(np.abs(hl - want_hl)))
+    say(f"7B prefill: head logits err {herr2:.3e}")
+    assert herr2 <= tol.logits
     checked = 0
     for i in range(cfg["n_cerb_heads"]):
-        tol_i = H.head_logit_tol(tol, want[i])
-        assert float(np.max(np.abs(hl[i] - want[i]))) <= tol_i, (i, tol_i)
-        s = -np.sort(-want[i])[:K + 1]
-        for j in range(K):
-            if H._margin_ok(s, j, tol_i):
+        srt_i = -np.sort(-want_hl[i])[:cfg["topk"] + 1]
+        ids = orc.topk_ids(want_hl[i], cfg["topk"])
+        for j in range(cfg["topk"]):
+            if H._margin_ok(srt_i, j, tol.logits):
                 checked += 1
-                assert cand_gpu[i, j] == out["cand"][i, j], (i, j)
-    say(f"{tag}: candidates checked {checked}/{cfg['n_cerb_heads'] * K}")
+                assert int(st.cand[0, i, j]) == int(ids[j]), (i, j)
+    assert checked > 0
 
 
 # ---------------------------------------------------------------------------------------------
@@ -1004,8 +1146,10 @@ def test_7b_gated_256_step_schedule(pair_7b):
 
 # ---------------------------------------------------------------------------------------------
 # configs[4]: eight independent 7B-shape sequences, prefixes drawn from 512..4096, per-sequence
-# gate decisions, one launch.  The oracle checks one sampled root-to-leaf path of a tree sequence
-# and the single row of an auto-regressive one.
+# gate decisions drawn Bernoulli(0.3), one launch.  For every one of the eight sequences the oracle
+# runs one root-to-leaf path of a tree sequence as a chain tree (a node's result depends only on the
+# prefix and its ancestors, so the chain's rows must equal those rows of the full tree pass), or the
+# single row of an auto-regressive one.
 # ---------------------------------------------------------------------------------------------
 def test_7b_batch8_mixed_launch(pair_7b):
     Bn, cap = 8, 4224
@@ -1024,38 +1168,54 @@ def test_7b_batch8_mixed_launch(pair_7b):
     st.cand.copy_(cands.cuda())
     st.gate_flag.copy_(torch.from_numpy(flags).cuda())
     taps = pair.taps()
-    kv_before = {b: st.kv[:, :, b].clone() for b in (0, 1)}
     pair.engine.verify_step(st, Bn)
     torch.cuda.synchronize()
     assert int(st.status[0]) == 0
     rows = int(np.sum(np.where(flags == 1, 1, T)))
-    say(f"7B batch 8: prefixes {Ls.tolist()}, flags {flags.tolist()}, {rows} packed rows")
+    say(f"7B batch 8: prefixes {Ls.tolist()} (sum {int(Ls.sum())}), flags {flags.tolist()}, {rows} packed rows")
+    # a different root-to-leaf path per tree sequence: the leaves in turn, deepest first
     depth, _ = orc.tree_tables(pair.parent)
-    leaf = max(n for n in range(T) if depth[n] == cfg["n_cerb_heads"])
-    for b in (0, 1):
+    leaves = sorted((n for n in range(T) if n not in set(pair.parent)), key=lambda n: (-depth[n], -n))
+    worst = 0.0
+    for b in range(Bn):
         nodes = []
-        n = leaf if flags[b] == 0 else 0
+        n = leaves[(5 * b) % len(leaves)] if flags[b] == 0 else 0
         while n >= 0:
             nodes.append(n)
             n = pair.parent[n]
         nodes.reverse()
         chain_parent = [-1] + list(range(len(nodes) - 1))
         chain_rank = [pair.rank[n] for n in nodes]
-        kvb = kv_before[b]
-        kv_host = [(kvb[l, 0].double().cpu().numpy(), kvb[l, 1].double().cpu().numpy()) for l in range(cfg["n_layers"])]
-        ost = orc.new_state(kv_host, int(Ls[b]), int(roots[b]), cands[b].numpy(), 0)
+        Lb = int(Ls[b])
+        kv_host = []
+        for l in range(cfg["n_layers"]):              # the step leaves the committed rows 0..L-1 as they were
+            K = np.zeros((cfg["n_heads"], Lb + len(nodes), cfg["head_dim"]))
+            V = np.zeros_like(K)
+            K[:, :Lb] = st.kv[l, 0, b, :, :Lb].double().cpu().numpy()
+            V[:, :Lb] = st.kv[l, 1, b, :, :Lb].double().cpu().numpy()
+            kv_host.append((K, V))
+        ost = orc.new_state(kv_host, Lb, int(roots[b]), cands[b].numpy(), 0)
         out = orc.verify_step(cfg, pair.W, chain_parent, chain_rank, ost)
         idx = torch.tensor([b * T + n for n in nodes])
         assert np.array_equal(taps.node_token[idx].cpu().numpy(), out["tok"])
         err = float(np.max(np.abs(taps.logits[idx].double().cpu().numpy() - out["logits"])))
-        say(f"7B batch 8 seq {b} (L={Ls[b]}, flag={flags[b]}): logits max-abs err {err:.3e} on nodes {nodes}")
-        assert err <= tol.logits
+        herr = float(np.max(np.abs(taps.h_last[idx].double().cpu().numpy() - out["h_last"])))
+        worst = max(worst, err)
+        say(f"7B batch 8 seq {b} (L={Lb}, flag={flags[b]}): logits max-abs err {err:.3e}, h_last err {herr:.3e} on nodes {nodes}")
+        assert err <= tol.logits and herr <= tol.hidden
         srt = -np.sort(-out["logits"], axis=1)
         safe = (srt[:, 0] - srt[:, 1]) > 2 * tol.logits
         assert np.array_equal(taps.node_argmax[idx].cpu().numpy()[safe], np.argmax(out["logits"], axis=1)[safe])
         # random candidates never match the model's own token: only the root is accepted
         if safe[0]:
             assert int(st.accept_len[b]) == 1 == out["accept_len"]
-            assert int(st.kv_len[b]) == Ls[b] + 1 and int(st.root_token[b]) == out["root"]
+            assert int(st.kv_len[b]) == Lb + 1 and int(st.root_token[b]) == out["root"]
             assert abs(float(st.entropy[b]) - out["entropy"]) <= tol.entropy
+            # the committed row of every layer
+            for l in (0, cfg["n_layers"] // 2, cfg["n_layers"] - 1):
+                for kvi in (0, 1):
+                    got = st.kv[l, kvi, b, :, Lb].double().cpu().numpy()
+                    want = ost["kv"][l][kvi][:, Lb]
+                    assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (b, l, kvi)
+    say(f"7B batch 8: all {Bn} sequences compared, worst logits err {worst:.3e}")
     pair.engine.close()
