@@ -69,6 +69,16 @@ def round_oracle_kv(ost: dict, dtype: int) -> None:
                         torch.from_numpy(V).to(tdt).to(torch.float64).numpy())
 
 
+def kv_mismatch(got: np.ndarray, want: np.ndarray, tol: Tol) -> Optional[str]:
+    """None if every cache element is within kv_atol + kv_rtol * |want|, else the worst offender."""
+    excess = np.abs(got - want) - (tol.kv_atol + tol.kv_rtol * np.abs(want))
+    if not (excess > 0).any():
+        return None
+    i = np.unravel_index(int(np.argmax(excess)), excess.shape)
+    return (f"{int((excess > 0).sum())} of {excess.size} elements out of tolerance; worst at {tuple(int(k) for k in i)}: "
+            f"got {got[i]!r} want {want[i]!r} (max-abs difference overall {float(np.max(np.abs(got - want))):.3e})")
+
+
 def head_logit_tol(tol: Tol, want: np.ndarray) -> float:
     """Tolerance on one decoding head's logits: the same flat max-abs bar as the LM head's (the
     task statement gives one bar for logits), whatever the scale of the head's logits."""
@@ -156,8 +166,9 @@ def compare_step(cfg: dict, out: dict, st: B.DeviceState, taps: B.DeviceTaps, b:
             for kvi, ref in ((0, Ko), (1, Vo)):
                 got = st.kv[l, kvi, b, :, L0:L1].double().cpu().numpy()
                 want = ref[:, L0:L1]
-                if not np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol):
-                    bad(f"cache rows {L0}..{L1 - 1} layer {l} {'KV'[kvi]} differ by {np.max(np.abs(got - want)):.3e}")
+                mm = kv_mismatch(got, want, tol)
+                if mm:
+                    bad(f"cache rows {L0}..{L1 - 1} layer {l} {'KV'[kvi]}: {mm}")
                     break
 
         S_gpu = float(st.entropy[b])

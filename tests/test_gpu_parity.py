@@ -1,6 +1,7 @@
 """GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle on the
 same seeded inputs.  Run with `-m gpu` on an MI355X."""
 import copy
+import dataclasses
 import sys
 
 import numpy as np
@@ -333,7 +334,8 @@ def test_prefill_seeds_the_first_step(tiny_pairs, dtype, n_prompt):
         for kvi in (0, 1):
             got = st.kv[l, kvi, 0, :, :n_prompt].double().cpu().numpy()
             want = ost["kv"][l][kvi][:, :n_prompt]
-            assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, float(np.max(np.abs(got - want))))
+            mm = H.kv_mismatch(got, want, tol)
+            assert mm is None, (l, kvi, mm)
     P = B.CERBERUS_MAX_TREE                    # rows of a full pass
     n_last = n_prompt % P or P                 # rows of the last pass: the taps hold its first T rows at slots 0..
     k, first = min(n_last, T), n_prompt - n_last
@@ -739,7 +741,12 @@ def test_tiny_tuning_knobs_do_not_change_results(params):
     out = pair.oracle_step(ost)
     pair.engine.verify_step(st, 1)
     torch.cuda.synchronize()
-    rep = H.compare_step(cfg, out, st, taps, 0, pair.T, BF16, ost, tol=H.TOL_BF16)
+    tol = H.TOL_BF16
+    if params.get("act_split") == 0:
+        # one bf16 plane: a GEMM input carries 8 significant bits instead of 16, so a new cache row is off
+        # by up to 2^-9 relative before its own rounding to bf16: up to two rounding steps apart
+        tol = dataclasses.replace(tol, kv_atol=1e-2, kv_rtol=1.6e-2)
+    rep = H.compare_step(cfg, out, st, taps, 0, pair.T, BF16, ost, tol=tol)
     say(f"  {params}: logits err {rep.max_logit_err:.2e}")
     assert not rep.failures, f"{params}: " + "; ".join(rep.failures)
     pair.engine.close()
@@ -987,6 +994,7 @@ def test_7b_decode_two_chained_steps_match_oracle(pair_7b):
     assert int(st.kv_len[0]) == L + len(got)
 
     ost = orc.new_state(kv_host, L, root, cand.numpy(), 0)
+    depth, _ = orc.tree_tables(pair.parent)
     want, clear = [], True
     for step in range(2):
         if step == 1:                                # the device's second step read bf16 cache rows
@@ -994,12 +1002,30 @@ def test_7b_decode_two_chained_steps_match_oracle(pair_7b):
         out = orc.verify_step(cfg, pair.W, pair.parent, pair.rank, ost)
         srt = -np.sort(-out["logits"][out["path"]], axis=1)
         margin = float(np.min(srt[:, 0] - srt[:, 1]))
-        cmargin = min(float(np.min(-np.diff(-np.sort(-hl)[:cfg["topk"] + 1]))) for hl in out["head_logits"])
-        say(f"  7B decode step {step}: accept {out['accept_len']}, argmax margin {margin:.2e}, candidate margin {cmargin:.2e}")
-        if margin <= 2 * tol.logits or (step == 0 and cmargin <= 2 * tol.logits):
+        say(f"  7B decode step {step}: accept {out['accept_len']}, argmax margin {margin:.2e}")
+        if margin <= 2 * tol.logits:
             clear = False
             break
         want += [int(t) for t in out["committed"]]
+        if step == 0:
+            # The second step's tree carries the first step's candidates.  Where two head logits of the
+            # oracle lie within the tolerance their order is not decided, so the device's own choice is
+            # read back from its second step's node tokens, checked wherever the margin is clear, and
+            # the oracle continues from it.
+            tok2 = taps.node_token[:T].cpu().numpy()
+            assert int(tok2[0]) == out["root"]
+            cand_dev = np.array(ost["cand"])
+            checked = 0
+            for n in range(1, T):
+                i, j = depth[n] - 1, pair.rank[n]
+                s_i = -np.sort(-out["head_logits"][i])[:cfg["topk"] + 1]
+                if H._margin_ok(s_i, j, tol.logits):
+                    checked += 1
+                    assert int(tok2[n]) == int(ost["cand"][i, j]), (n, i, j)
+                cand_dev[i, j] = int(tok2[n])
+            say(f"  7B decode: {checked}/{T - 1} tree tokens of the second step checked against the oracle's candidates")
+            assert checked > 0
+            ost["cand"] = cand_dev
     assert got[:len(want)] == want and len(want) >= 1
     if clear:
         assert len(got) == len(want)
@@ -1007,7 +1033,7 @@ def test_7b_decode_two_chained_steps_match_oracle(pair_7b):
         say(f"  7B decode, second step: logits err {rep.max_logit_err:.3e}, head logits err {rep.max_head_logit_err:.3e}")
         assert not rep.failures, "; ".join(rep.failures)
     else:
-        say("  7B decode: a decision of the first step sits within the tolerance; compared the log up to it")
+        say("  7B decode: an argmax of the committed path sits within the tolerance; compared the log up to it")
 
 
 def test_7b_prefill_two_passes_matches_oracle(pair_7b):
@@ -1047,7 +1073,8 @@ def test_7b_prefill_two_passes_matches_oracle(pair_7b):
         for kvi in (0, 1):
             got = st.kv[l, kvi, 0, :, :n_prompt].double().cpu().numpy()
             want = kv[l][kvi][:, :n_prompt]
-            assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (l, kvi, float(np.max(np.abs(got - want))))
+            mm = H.kv_mismatch(got, want, tol)
+            assert mm is None, (l, kvi, mm)
     n_last = n_prompt % P or P
     k, first = min(n_last, T), n_prompt - n_last
     err = float(np.max(np.abs(taps.logits[:k].double().cpu().numpy() - logits[first:first + k])))
@@ -1216,6 +1243,7 @@ def test_7b_batch8_mixed_launch(pair_7b):
                 for kvi in (0, 1):
                     got = st.kv[l, kvi, b, :, Lb].double().cpu().numpy()
                     want = ost["kv"][l][kvi][:, Lb]
-                    assert np.allclose(got, want, atol=tol.kv_atol, rtol=tol.kv_rtol), (b, l, kvi)
+                    mm = H.kv_mismatch(got, want, tol)
+                    assert mm is None, (b, l, kvi, mm)
     say(f"7B batch 8: all {Bn} sequences compared, worst logits err {worst:.3e}")
     pair.engine.close()
