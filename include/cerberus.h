@@ -115,7 +115,8 @@ typedef struct {
   int32_t *status;          /* one sticky word, OR of CERBERUS_DEV_* bits                     */
 } cerberus_state;
 
-/* Optional taps for tests and benchmarks, all DEVICE, any may be NULL.  Outputs are written by
+/* Optional taps for tests and benchmarks (one struct standing for both a "set overrides" and a "debug
+ * outputs" call), all DEVICE, any may be NULL.  Outputs are written by
  * the next steps; `forced_*` replace computed values.  Row index of node n of sequence b is
  * b*T + n.                                                                                   */
 typedef struct {
@@ -148,7 +149,8 @@ int cerberus_ar_step(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch,
 
 /* Prompt phase of Algorithm 1 (lines 1-5) for sequence `seq` of the batch: a causal forward of
  * `n_tokens` prompt tokens (DEVICE int32) appended at cache rows kv_len.., in passes of up to
- * CERBERUS_MAX_TREE rows (the result does not depend on the pass size), then on the last position the LM head (-> root_token), the
+ * CERBERUS_MAX_TREE rows (the result does not depend on the pass size up to the rounding of the cache: rows
+ * of earlier passes are read back from the cache in its storage type), then on the last position the LM head (-> root_token), the
  * gate (-> gate_flag, entropy) and, where the gate says parallel, the heads (-> cand): the state a
  * first decoding step starts from.  kv_len[seq] advances by n_tokens; accept_len[seq] is set to 0;
  * the other sequences of the batch are not touched.  Tokens outside the vocabulary count as token 0
@@ -172,7 +174,9 @@ int cerberus_decode(cerberus_ctx *ctx, const cerberus_state *st, int32_t batch, 
 int cerberus_gate(cerberus_ctx *ctx, const float *hidden, int32_t rows, float *entropy_out,
                   int32_t *flag_out, void *stream);
 
-/* Acceptance and compaction alone: node_argmax / node_token are DEVICE [batch*T]; every
+/* Acceptance and compaction alone (Section 3.1 names tree verification but gives no rule; this is the
+ * greedy longest-prefix reading: walk from the root while a child carries the base model's own next
+ * token).  node_argmax / node_token are DEVICE [batch*T]; every
  * sequence is taken to have run the whole tree, its K/V in cache rows kv_len..kv_len+T-1.
  * Writes accept_len, accepted_*, root_token, moves cache rows and advances kv_len.            */
 int cerberus_accept(cerberus_ctx *ctx, const int32_t *node_argmax, const int32_t *node_token,

@@ -117,9 +117,14 @@ __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr,
   }
   __syncthreads();
   if (t == 0) {
+    // rows pack back to back; with the caller's per-node arrays of the acceptance entry point
+    // (ASSEMBLE_FULL_TREE) sequence b owns rows b*T.. whether or not an earlier sequence sits out
     int r = 0;
-    for (int b = 0; b < batch; ++b) { sRow0[b] = r; r += sT[b]; }
-    *rm.n_rows = r;
+    for (int b = 0; b < batch; ++b) {
+      sRow0[b] = mode == ASSEMBLE_FULL_TREE ? b * tr.T : r;
+      r += sT[b];
+    }
+    *rm.n_rows = mode == ASSEMBLE_FULL_TREE ? batch * tr.T : r;
   }
   __syncthreads();
   if (t < batch) { rm.seq_T[t] = sT[t]; rm.seq_L[t] = sL[t]; rm.seq_row0[t] = sRow0[t]; }

@@ -32,8 +32,11 @@ TOL_F32 = Tol(logits=5e-5, hidden=5e-5, entropy=1e-5, kv_atol=2e-5, kv_rtol=2e-5
 # is 5e-4, and the gate flag is compared whenever |S - T| exceeds twice the bar = 1e-3 bits.  kv: a cache row
 # is one bf16 rounding (relative 2^-8 = 3.9e-3) of a value of magnitude up to ~6, plus the error of
 # the row before rounding, which can move the rounding by one step: two steps of 2^-8 relative
-# (kv_rtol 8e-3); the absolute floor covers values near zero (value error measured: 2e-4).
-TOL_BF16 = Tol(logits=2e-2, hidden=2e-2, entropy=5e-4, kv_atol=2e-3, kv_rtol=8e-3)
+# (kv_rtol 8e-3).  The absolute part is the error of the row's value before rounding: K and V are
+# activations of the same scale as the logits (std ~1.3), so half the logits bar; measured 2e-4 on a
+# step whose inputs match exactly and up to 4e-3 on rows computed from bf16 cache rows that themselves
+# differ from the oracle's by one rounding step (second prompt pass, second chained step).
+TOL_BF16 = Tol(logits=2e-2, hidden=2e-2, entropy=5e-4, kv_atol=1e-2, kv_rtol=8e-3)
 # the two-layer tiny model amplifies nothing: with hi+lo bf16 GEMM inputs its logits sit within 2e-4
 # of the oracle, so the tiny-shape tests use a ten times tighter bar (more integer decisions checked)
 TOL_BF16_TINY = Tol(logits=2e-3, hidden=4e-3, entropy=5e-4, kv_atol=2e-3, kv_rtol=8e-3)
