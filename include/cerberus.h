@@ -182,6 +182,17 @@ int cerberus_gate(cerberus_ctx *ctx, const float *hidden, int32_t rows, float *e
 int cerberus_accept(cerberus_ctx *ctx, const int32_t *node_argmax, const int32_t *node_token,
                     const cerberus_state *st, int32_t batch, void *stream);
 
+/* cerberus_accept for callers that cannot allocate device memory or hand over a workspace for it
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same inputs,
+ * outputs and result, but the kernels' scratch (row map, accepted path, last-row list) lives in a
+ * static device array of the library, 32 KB per GPU, held until the process ends.  Limits: up to
+ * CERBERUS_MAX_BATCH sequences and 1024 tree rows in all (batch * n_nodes); larger calls return
+ * CERBERUS_ERR_CAPACITY.  It calls no allocating routine.  All calls on one GPU share that GPU's
+ * array: calls that overlap on one GPU (two streams, two contexts) race; calls in stream order do not.
+ * The array's address is resolved by cerberus_init on the context's device.                    */
+int cerberus_accept_noalloc(cerberus_ctx *ctx, const int32_t *node_argmax, const int32_t *node_token,
+                            const cerberus_state *st, int32_t batch, void *stream);
+
 /* Installs (or, with NULL, clears) the taps; the struct is copied.                             */
 int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
 

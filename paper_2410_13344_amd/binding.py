@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
         L.cerberus_gate.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.cerberus_accept.restype = C.c_int
         L.cerberus_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(State), C.c_int32, C.c_void_p]
+        L.cerberus_accept_noalloc.restype = C.c_int
+        L.cerberus_accept_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(State), C.c_int32, C.c_void_p]
         L.cerberus_set_taps.restype = C.c_int
         L.cerberus_set_taps.argtypes = [C.c_void_p, C.POINTER(Taps)]
         L.cerberus_set_param.restype = C.c_int
@@ -198,6 +200,12 @@ def cerberus_accept(ctx: int, node_argmax: torch.Tensor, node_token: torch.Tenso
                     stream=None) -> None:
     _check(lib().cerberus_accept(ctx, node_argmax.data_ptr(), node_token.data_ptr(), C.byref(state), batch,
                                  _stream_ptr(stream)))
+
+
+def cerberus_accept_noalloc(ctx: int, node_argmax: torch.Tensor, node_token: torch.Tensor, state: State, batch: int,
+                            stream=None) -> None:
+    _check(lib().cerberus_accept_noalloc(ctx, node_argmax.data_ptr(), node_token.data_ptr(), C.byref(state), batch,
+                                         _stream_ptr(stream)))
 
 
 def cerberus_set_taps(ctx: int, taps: Optional[Taps]) -> None:

@@ -91,6 +91,29 @@ struct cerberus_ctx {
 
 namespace {
 
+// Scratch of cerberus_accept_noalloc (the acceptance entry point for callers that cannot pass or
+// allocate a workspace): the row map, the accepted path and the last-row list, for up to
+// kNoAllocBatch sequences and kNoAllocRows tree rows in all.  One copy of the array per GPU, held
+// until the process ends; its address on a device is resolved once, at cerberus_init on that device.
+constexpr int kNoAllocBatch = CERBERUS_MAX_BATCH;
+constexpr int kNoAllocRows = 1024;
+constexpr int kNoAllocPath = CERBERUS_MAX_HEADS + 1;
+constexpr size_t kNoAllocScratchBytes = 32768;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// with the context's device current
+int resolve_static_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return fail(CERBERUS_ERR_ARG, "device index %d out of 0..%d", device, kMaxDevices - 1);
+  if (g_scratch_ptr[device]) return CERBERUS_OK;
+  void* p = nullptr;
+  hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !p) return fail(CERBERUS_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+  g_scratch_ptr[device] = reinterpret_cast<unsigned char*>(p);
+  return CERBERUS_OK;
+}
+
 int head_width(const cerberus_config& c, int i, int s) {
   return (i >= 1 && c.special_block >= 0 && s >= c.special_block) ? 2 * c.d_model : c.d_model;
 }
@@ -564,6 +587,7 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   } while (0)
 
   HIP_INIT(hipGetDevice(&c->device));
+  { const int rc = resolve_static_scratch(c->device); if (rc != CERBERUS_OK) return cleanup(rc); }
   HIP_INIT(hipMemset(workspace, 0, c->small_bytes));
   HIP_INIT(hipMemcpy((void*)c->tree.parent, c->parent.data(), T * sizeof(int), hipMemcpyHostToDevice));
   HIP_INIT(hipMemcpy((void*)c->tree.rank, c->rank.data(), T * sizeof(int), hipMemcpyHostToDevice));
@@ -681,6 +705,40 @@ int cerberus_accept(cerberus_ctx* ctx, const int32_t* node_argmax, const int32_t
   HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, s));
   HIP_TRY(launch_accept(ctx->D, ctx->tree, ctx->rm, node_argmax, node_token, *st, ctx->path, ctx->last_row, batch, s));
   HIP_TRY(launch_compact(ctx->D, ctx->rm, *st, ctx->path, batch, s));
+  return CERBERUS_OK;
+}
+
+int cerberus_accept_noalloc(cerberus_ctx* ctx, const int32_t* node_argmax, const int32_t* node_token, const cerberus_state* st,
+                            int32_t batch, void* stream) {
+  TRY(check_state(ctx, st, batch));
+  if (!node_argmax || !node_token) return fail(CERBERUS_ERR_ARG, "null node arrays");
+  const Dims& D = ctx->D;
+  if (batch > kNoAllocBatch || batch * D.T > kNoAllocRows || D.Hc + 1 > kNoAllocPath)
+    return fail(CERBERUS_ERR_CAPACITY, "cerberus_accept_noalloc takes up to %d sequences, %d tree rows in all and %d heads; got %d x %d rows, %d heads",
+                kNoAllocBatch, kNoAllocRows, kNoAllocPath - 1, batch, D.T, D.Hc);
+  if (ctx->device < 0 || ctx->device >= kMaxDevices || !g_scratch_ptr[ctx->device])
+    return fail(CERBERUS_ERR_HIP, "the static scratch array of device %d was not resolved at cerberus_init", ctx->device);
+  // carve the row map, the path and the last-row list out of this device's copy of the array
+  Bump b{g_scratch_ptr[ctx->device], 0};
+  RowMap rm{};
+  rm.n_rows = b.take<int>(1);
+  rm.seq_row0 = b.take<int>(kNoAllocBatch);
+  rm.seq_T = b.take<int>(kNoAllocBatch);
+  rm.seq_L = b.take<int>(kNoAllocBatch);
+  rm.row_seq = b.take<int>(kNoAllocRows);
+  rm.row_node = b.take<int>(kNoAllocRows);
+  rm.row_pos = b.take<int>(kNoAllocRows);
+  rm.row_tok = b.take<int>(kNoAllocRows);
+  int* path = b.take<int>((size_t)kNoAllocBatch * kNoAllocPath);
+  int* last_row = b.take<int>(kNoAllocBatch);
+  if (b.off > kNoAllocScratchBytes) return fail(CERBERUS_ERR_CAPACITY, "static scratch layout exceeds the array");
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  cerberus_taps none{};
+  // every word the three kernels read from the array is written by an earlier one of them in this call
+  // (the assembly writes the map of all `batch` sequences), so nothing has to start at zero
+  HIP_TRY(launch_assemble(D, ctx->tree, rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, s));
+  HIP_TRY(launch_accept(D, ctx->tree, rm, node_argmax, node_token, *st, path, last_row, batch, s));
+  HIP_TRY(launch_compact(D, rm, *st, path, batch, s));
   return CERBERUS_OK;
 }
 
