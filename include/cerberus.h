@@ -207,7 +207,11 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)
  *   "attn_chunk"      (128 or 256, default 128) committed cache rows per attention workgroup
- *   "attn_mfma"       (0 or 1, default 1)      0: plain attention kernel instead of the MFMA one     */
+ *   "attn_mfma"       (0 or 1, default 1)      0: plain attention kernel instead of the MFMA one
+ *   "gemm_fused"      (0 or 1, default 1)      1: bf16 launches of up to 64 rows run QKV + RoPE + KV write and
+ *                                              gate/up + SwiGLU as one whole-K launch each (where the shapes
+ *                                              allow: at most 6 slabs of 16 columns per compute unit); 0: split-K
+ *                                              GEMM plus a separate RoPE / SwiGLU launch, as for larger launches */
 int cerberus_set_param(cerberus_ctx *ctx, const char *name, int32_t value);
 
 /* Benchmark hook: enqueues back to back, for every layer (or head stage), the GEMM launches of

@@ -61,6 +61,7 @@ struct cerberus_ctx {
   TreeDev tree{};
   RowMap rm{};
   double* inv_freq = nullptr;
+  float2* rope_cs = nullptr;   // [rows][dh/2] (cos, sin) of this launch's row positions
   int *last_row = nullptr, *path = nullptr, *g = nullptr;
   float* topk_v = nullptr;   // per-slice candidate lists of the heads' top-k: [Hc][Bmax][TOPK_MAX_PARTS][CERBERUS_MAX_TOPK]
   int* topk_i = nullptr;
@@ -85,11 +86,19 @@ struct cerberus_ctx {
   int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1, attn_chunk = 128, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
+
+  // whole-K fused GEMMs (bf16 mode, launches of up to 64 rows): which slabs every workgroup owns
+  int fused_grid = 0;                    // workgroups = compute units of the device (0: not set up)
+  int *slabs_qkv = nullptr, *slabs_gu = nullptr;   // device tables [kFusedMaxGrid][ns]
+  int ns_qkv = 0, ns_gu = 0;             // positions per workgroup; 0 = that GEMM stays on the split-K path
+  int use_fused = 1;
   void* workspace = nullptr;
   size_t workspace_bytes = 0;
 };
 
 namespace {
+
+constexpr int kFusedMaxGrid = 512, kFusedMaxNs = 6;
 
 // Scratch of cerberus_accept_noalloc (the acceptance entry point for callers that cannot pass or
 // allocate a workspace): the row map, the accepted path and the last-row list, for up to
@@ -188,6 +197,7 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->chain.aw = ceil_div(P, 64);
   c->chain.anc = b.take<unsigned long long>((size_t)P * c->chain.aw);
   c->inv_freq = b.take<double>(D.dh / 2);
+  c->rope_cs = b.take<float2>((size_t)std::max(B * T, c->prompt_rows) * (D.dh / 2));
   c->rm.n_rows = b.take<int>(1);
   c->rm.seq_row0 = b.take<int>(B);
   c->rm.seq_T = b.take<int>(B);
@@ -232,6 +242,10 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->res_b.assign((size_t)D.Hc * D.R, nullptr);
   for (int i = 0; i < D.Hc; ++i)
     for (int s = 0; s < D.R; ++s) c->res_b[i * D.R + s] = b.take<float>(head_width(cfg, i, s));
+  if (cfg.dtype == CERBERUS_BF16) {
+    c->slabs_qkv = b.take<int>((size_t)kFusedMaxGrid * kFusedMaxNs);
+    c->slabs_gu = b.take<int>((size_t)kFusedMaxGrid * kFusedMaxNs);
+  }
   c->small_bytes = align_up(b.off, 256);
   if (cfg.dtype == CERBERUS_BF16) {
     auto pk = [&](int N, int K) { return (void*)b.take<bf16_t>((size_t)N * kpad(cfg, K)); };
@@ -333,6 +347,55 @@ void plan_gemm(const cerberus_ctx* c, GemmBatch& g, int nprob, const void* const
   split_plan(c, g, 64);
 }
 
+// Slab tables of the whole-K fused GEMMs for a grid of `grid` workgroups.  Positions (2p, 2p+1) of a
+// workgroup hold what its epilogue needs together: slabs i and i + dh/32 of a q or k head (RoPE rotates column
+// j with j + dh/2), one or two v slabs, or the gate and the up slab of 16 FFN columns.  Work is dealt so that
+// the workgroups' slab counts differ by as little as the pairing allows.  Returns the positions per workgroup
+// (0 if more than kFusedMaxNs would be needed).
+int fused_tables(const Dims& D, int grid, std::vector<int>& qkv, int& ns_qkv, std::vector<int>& gu, int& ns_gu) {
+  const int spd = D.d / 16, sph = D.dh / 16;
+  std::vector<std::vector<int>> pos(grid);       // per workgroup: flat list of positions
+  auto load = [&](int w) { int n = 0; for (int v : pos[w]) n += v >= 0; return n; };
+  auto lightest = [&]() { int best = 0; for (int w = 1; w < grid; ++w) if (load(w) < load(best)) best = w; return best; };
+  int w = 0;
+  for (int sec = 0; sec < 2; ++sec)
+    for (int h = 0; h < D.nH; ++h)
+      for (int i = 0; i < sph / 2; ++i) {
+        const int lo = sec * spd + h * sph + i;
+        pos[w].push_back(lo); pos[w].push_back(lo + sph / 2);
+        w = (w + 1) % grid;
+      }
+  for (int t = 0; t < spd; ++t) {
+    const int sv = 2 * spd + t, best = lightest();
+    std::vector<int>& P = pos[best];
+    if (P.size() % 2 == 1) P.push_back(sv);      // joins the v slab that stood alone at the end
+    else P.push_back(sv);                        // stands alone at the end (an odd number of positions) for now
+  }
+  // a list of odd length ends in a single v slab; lists are padded with -1 up to the common width
+  size_t mx = 0;
+  for (auto& P : pos) mx = std::max(mx, P.size());
+  ns_qkv = mx <= (size_t)kFusedMaxNs ? (int)std::max<size_t>(mx, 2) : 0;
+  qkv.assign((size_t)grid * std::max(ns_qkv, 1), -1);
+  if (ns_qkv)
+    for (int g = 0; g < grid; ++g) std::copy(pos[g].begin(), pos[g].end(), qkv.begin() + (size_t)g * ns_qkv);
+
+  ns_gu = 0;
+  gu.clear();
+  if (D.F % 16 == 0) {
+    const int fs = D.F / 16, per = ceil_div(fs, grid);
+    if (2 * per <= kFusedMaxNs) {
+      ns_gu = 2 * per;
+      gu.assign((size_t)grid * ns_gu, -1);
+      for (int s2 = 0; s2 < fs; ++s2) {
+        const int g = s2 % grid, p = s2 / grid;
+        gu[(size_t)g * ns_gu + 2 * p] = s2;
+        gu[(size_t)g * ns_gu + 2 * p + 1] = fs + s2;
+      }
+    }
+  }
+  return ns_qkv;
+}
+
 void build_plans(cerberus_ctx* c) {
   const Dims& D = c->D;
   const int d = D.d, L = D.n_layers;
@@ -408,18 +471,30 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
   const Dims& D = c->D;
   const RowMap& rm = c->rm;
   const size_t kv_layer_bytes = (size_t)2 * D.Bmax * D.nH * D.cap * D.dh * c->elem;
-  HIP_TRY(launch_embed(D, rm, c->embed, c->x, rows_max, s));
+  HIP_TRY(launch_embed(D, rm, c->embed, c->x, c->inv_freq, c->rope_cs, rows_max, s));
 
   GemmProb pd{};                   // GEMM whose partials are the pending residual
   const GemmProb* prev = nullptr;
+  // launches of up to 64 rows: QKV + RoPE + KV write and gate/up + SwiGLU as one whole-K launch each
+  const bool fused = c->use_fused && D.dtype == CERBERUS_BF16 && rows_max <= 64 && c->fused_grid > 0 && c->act_split == 1;
+  const bool fq = fused && c->ns_qkv > 0, fg = fused && c->ns_gu > 0;
+  const int nb = add_gain_blocks(D.d);
   for (int l = 0; l < D.n_layers; ++l) {
     HIP_TRY(launch_add_gain(D, rm, c->x, prev ? prev->out : nullptr, prev ? prev->S : 0,
-                            prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, c->ssq, rows_max, s));
+                            prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, c->ssq, rows_max, s, fq));
     GemmProb pq, po, pg;
-    TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pq));
     void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
-    HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->inv_freq, c->q, kv_layer, c->ktree, c->vtree,
-                           c->ssq, rows_max, s));
+    if (fq) {
+      FusedQkvArgs fa{};
+      fa.W = c->wqkv[l]; fa.At = c->xn; fa.slabs = c->slabs_qkv; fa.ksteps = kpad(c->cfg, D.d) / 32; fa.ssq = c->ssq; fa.nb = nb;
+      fa.rope_cs = c->rope_cs; fa.rm = rm; fa.q = (bf16_t*)c->q; fa.kv_layer = (bf16_t*)kv_layer; fa.ktree = (bf16_t*)c->ktree;
+      fa.vtree = (bf16_t*)c->vtree; fa.lo_off = (size_t)c->R64 * D.d; fa.D = D;
+      HIP_TRY(launch_qkv_rope(fa, c->ns_qkv, c->fused_grid, s));
+    } else {
+      TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pq));
+      HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->rope_cs, c->q, kv_layer, c->ktree, c->vtree,
+                             c->ssq, rows_max, s));
+    }
     AttnArgs aa{};
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
     aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)tr.T, 64); aa.tc_max = ceil_div(tr.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = tr.T;
@@ -427,9 +502,16 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
     aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &po));
-    HIP_TRY(launch_add_gain(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, c->ssq, rows_max, s));
-    TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pg));
-    HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, c->ssq, rows_max, s));
+    HIP_TRY(launch_add_gain(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, c->ssq, rows_max, s, fg));
+    if (fg) {
+      FusedGateUpArgs ga{};
+      ga.W = c->wgu[l]; ga.At = c->xn; ga.slabs = c->slabs_gu; ga.ksteps = kpad(c->cfg, D.d) / 32; ga.ssq = c->ssq; ga.nb = nb;
+      ga.d = D.d; ga.eps = D.eps; ga.rm = rm; ga.act = (bf16_t*)c->act; ga.lo_off = (size_t)c->R64 * D.Fpad; ga.Fpad = D.Fpad;
+      HIP_TRY(launch_gate_up_swiglu(ga, c->ns_gu, c->fused_grid, s));
+    } else {
+      TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pg));
+      HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, c->ssq, rows_max, s));
+    }
     TRY(run_gemm(c, c->p_down[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pd));
     prev = &pd;
   }
@@ -652,6 +734,15 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
       c->head_fc[i] = c->pk_fc[i];
     }
   }
+  if (D.dtype == CERBERUS_BF16) {
+    hipDeviceProp_t prop;
+    HIP_INIT(hipGetDeviceProperties(&prop, c->device));
+    c->fused_grid = std::min(prop.multiProcessorCount, (int)kFusedMaxGrid);
+    std::vector<int> tq, tg;
+    fused_tables(D, c->fused_grid, tq, c->ns_qkv, tg, c->ns_gu);
+    if (c->ns_qkv) HIP_INIT(hipMemcpy(c->slabs_qkv, tq.data(), tq.size() * sizeof(int), hipMemcpyHostToDevice));
+    if (c->ns_gu) HIP_INIT(hipMemcpy(c->slabs_gu, tg.data(), tg.size() * sizeof(int), hipMemcpyHostToDevice));
+  }
   HIP_INIT(hipDeviceSynchronize());
 #undef HIP_INIT
   build_plans(c);
@@ -806,6 +897,9 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
     if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "act_split must be 0 or 1");
     ctx->act_split = value;
     build_plans(ctx);
+  } else if (n == "gemm_fused") {
+    if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "gemm_fused must be 0 or 1");
+    ctx->use_fused = value;
   } else if (n == "gemm_max_split") {
     if (value < 1 || value > 16) return fail(CERBERUS_ERR_ARG, "gemm_max_split out of 1..16");
     ctx->max_split = value;

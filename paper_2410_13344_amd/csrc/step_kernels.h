@@ -39,16 +39,54 @@ hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, c
                            const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, hipStream_t s);
 hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, const int* g, int* last_row, int batch, int seq,
                                 int last_pass, hipStream_t s);
-hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, int rows_max, hipStream_t s);
+// also fills rope_cs[row][j] = (cos, sin)(pos(row) * inv_freq[j]), j < dh/2, the angle formed in double
+hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, const double* inv_freq, float2* rope_cs,
+                        int rows_max, hipStream_t s);
 hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
                               const float* gain, void* out, float* out_f32, float* tap, int rows_max, hipStream_t s);
 // residual add + x * gain + per-block sums of x^2 (the RMSNorm scalar is applied by the consumer of the next GEMM)
 int add_gain_blocks(int d);   // sums per row
+// a_tiled: write the GEMM input in MFMA A-fragment order (64 rows, see FusedQkvArgs) instead of row-major planes
 hipError_t launch_add_gain(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
-                           const float* gain, void* out, float* ssq, int rows_max, hipStream_t s);
+                           const float* gain, void* out, float* ssq, int rows_max, hipStream_t s, bool a_tiled = false);
 hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
-                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, const float* ssq,
+                          const float2* rope_cs, void* q, void* kv_layer, void* ktree, void* vtree, const float* ssq,
                           int rows_max, hipStream_t s);
+// Whole-K GEMMs with fused epilogues (gemm_fused.hip), launches of up to 64 rows in bf16 mode.
+// At: the GEMM input in MFMA A-fragment order, piece [((ks * 2 + plane) * 4 + mt) * 64 + lane] = the 8 values
+// of row mt*16 + lane%16 at columns ks*32 + (lane/16)*8.., plane 0 = hi, 1 = lo (written by launch_add_gain
+// with a_tiled).  slabs: [grid][ns] 16-column slabs of every workgroup, -1 = none; positions (2p, 2p+1) form a pair.
+struct FusedQkvArgs {
+  const void* W;            // packed [3d][K]
+  const void* At;
+  const int* slabs;         // pairs: slabs i and i + dh/32 of a q or k head; or one or two v slabs
+  int ksteps;               // padded K / 32
+  const float* ssq;         // block sums of x^2 of the pending attention norm
+  int nb;
+  const float2* rope_cs;    // [rows][dh/2] (cos, sin) of every row's rotation angles (written by launch_embed)
+  RowMap rm;
+  bf16_t* q;                // [rows][d] hi, lo plane lo_off later
+  bf16_t* kv_layer;         // [2][Bmax][nH][cap][dh]
+  bf16_t* ktree;
+  bf16_t* vtree;
+  size_t lo_off;
+  Dims D;
+};
+struct FusedGateUpArgs {
+  const void* W;            // packed [2F][K], gate rows first
+  const void* At;
+  const int* slabs;         // pairs: (gate slab s, up slab F/16 + s): the same 16 FFN columns
+  int ksteps;
+  const float* ssq;
+  int nb, d;
+  float eps;
+  RowMap rm;
+  bf16_t* act;              // [rows][Fpad] hi, lo plane lo_off later
+  size_t lo_off;
+  int Fpad;
+};
+hipError_t launch_qkv_rope(const FusedQkvArgs& a, int ns, int grid, hipStream_t s);
+hipError_t launch_gate_up_swiglu(const FusedGateUpArgs& a, int ns, int grid, hipStream_t s);
 hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
                          const float* ssq, int rows_max, hipStream_t s);
 hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, int* g,

@@ -181,9 +181,17 @@ hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, cons
 // x[row] = embedding of the row's token, widened to fp32; 512 threads, 8 consecutive elements each
 // per pass (d % 8 == 0)
 template <typename T>
-__global__ __launch_bounds__(512) void k_embed(const T* __restrict__ embed, const RowMap rm, float* __restrict__ x, int d) {
+__global__ __launch_bounds__(512) void k_embed(const T* __restrict__ embed, const RowMap rm, float* __restrict__ x, int d,
+                                               const double* __restrict__ inv_freq, float2* __restrict__ rope_cs, int half) {
   const int r = blockIdx.x;
   if (r >= *rm.n_rows) return;
+  // the row's RoPE rotations, the same in every layer: angle in double (at position ~4000 an fp32 product is
+  // already off by 1e-4 rad), stored as float
+  if ((int)threadIdx.x < half) {
+    double snd, csd;
+    sincos((double)rm.row_pos[r] * inv_freq[threadIdx.x], &snd, &csd);
+    rope_cs[(size_t)r * half + threadIdx.x] = make_float2((float)csd, (float)snd);
+  }
   const T* e = embed + (size_t)rm.row_tok[r] * d;
   for (int c = threadIdx.x * 8; c < d; c += 512 * 8) {
     float v[8];
@@ -205,9 +213,10 @@ __global__ __launch_bounds__(512) void k_embed(const T* __restrict__ embed, cons
   }
 }
 
-hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, int rows_max, hipStream_t s) {
-  if (D.dtype == 0) hipLaunchKernelGGL((k_embed<float>), dim3(rows_max), dim3(512), 0, s, (const float*)embed, rm, x, D.d);
-  else hipLaunchKernelGGL((k_embed<bf16_t>), dim3(rows_max), dim3(512), 0, s, (const bf16_t*)embed, rm, x, D.d);
+hipError_t launch_embed(const Dims& D, const RowMap& rm, const void* embed, float* x, const double* inv_freq, float2* rope_cs,
+                        int rows_max, hipStream_t s) {
+  if (D.dtype == 0) hipLaunchKernelGGL((k_embed<float>), dim3(rows_max), dim3(512), 0, s, (const float*)embed, rm, x, D.d, inv_freq, rope_cs, D.dh / 2);
+  else hipLaunchKernelGGL((k_embed<bf16_t>), dim3(rows_max), dim3(512), 0, s, (const bf16_t*)embed, rm, x, D.d, inv_freq, rope_cs, D.dh / 2);
   return hipGetLastError();
 }
 
@@ -282,7 +291,9 @@ hipError_t launch_add_rmsnorm(const Dims& D, const RowMap& rm, float* x, const f
 // split-K partials (k_rope_kv, k_swiglu) forms 1 / sqrt(mean x^2 + eps) from those sums and scales.
 // Four workgroups per row at d = 4096 instead of one.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int MAXS>
+// TILED (bf16 only): the GEMM input goes out in MFMA A-fragment order for the whole-K GEMMs: the 8 values of
+// row r at columns ks*32 + g*8.. form 16-byte piece ((ks*2 + plane)*4 + r/16)*64 + r%16 + 16*g, 64 rows in all.
+template <typename T, int MAXS, bool TILED>
 __global__ __launch_bounds__(256) void k_add_gain(float* __restrict__ x, const float* __restrict__ part, int S, size_t pstride,
                                                   const float* __restrict__ gain, T* __restrict__ out, size_t lo_off,
                                                   float* __restrict__ ssq, const RowMap rm, int d) {
@@ -301,8 +312,21 @@ __global__ __launch_bounds__(256) void k_add_gain(float* __restrict__ x, const f
     if (MAXS > 0) *reinterpret_cast<float4*>(xr) = v;
     ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     const float o[4] = {v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w};
+    if (TILED && sizeof(T) == 2) {
+      union { bf16_t h[4]; uint2 u; } hi, lo;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) st_a(out + (size_t)r * d + c + e, lo_off, o[e]);
+      for (int e = 0; e < 4; ++e) {
+        hi.h[e] = f32_to_bf16(o[e]);
+        lo.h[e] = f32_to_bf16(o[e] - bf16_to_f32(hi.h[e]));
+      }
+      const size_t piece = ((size_t)(c >> 5) * 8 + (r >> 4)) * 64 + (r & 15) + 16 * ((c & 31) >> 3);   // hi plane; lo: + 4 * 64
+      unsigned char* base = reinterpret_cast<unsigned char*>(out) + (c & 7) * 2;
+      *reinterpret_cast<uint2*>(base + piece * 16) = hi.u;
+      *reinterpret_cast<uint2*>(base + (piece + 256) * 16) = lo.u;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) st_a(out + (size_t)r * d + c + e, lo_off, o[e]);
+    }
   }
   ss = block_sum(ss, sh);
   if (threadIdx.x == 0) ssq[(size_t)r * nb + blockIdx.y] = ss;
@@ -311,14 +335,18 @@ __global__ __launch_bounds__(256) void k_add_gain(float* __restrict__ x, const f
 int add_gain_blocks(int d) { return (d + 1023) / 1024; }
 
 hipError_t launch_add_gain(const Dims& D, const RowMap& rm, float* x, const float* part, int S, size_t pstride,
-                           const float* gain, void* out, float* ssq, int rows_max, hipStream_t s) {
+                           const float* gain, void* out, float* ssq, int rows_max, hipStream_t s, bool a_tiled) {
   const dim3 grid(rows_max, add_gain_blocks(D.d));
+  if (a_tiled && (D.dtype == 0 || rows_max > 64)) return hipErrorInvalidValue;
 #define CERB_CALL(MS)                                                                                                  \
   if (D.dtype == 0)                                                                                                    \
-    hipLaunchKernelGGL((k_add_gain<float, MS>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (float*)out,         \
+    hipLaunchKernelGGL((k_add_gain<float, MS, false>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (float*)out,  \
                        (size_t)0, ssq, rm, D.d);                                                                       \
+  else if (a_tiled)                                                                                                    \
+    hipLaunchKernelGGL((k_add_gain<bf16_t, MS, true>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (bf16_t*)out, \
+                       (size_t)D.R64 * D.d, ssq, rm, D.d);                                                             \
   else                                                                                                                 \
-    hipLaunchKernelGGL((k_add_gain<bf16_t, MS>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (bf16_t*)out,       \
+    hipLaunchKernelGGL((k_add_gain<bf16_t, MS, false>), grid, dim3(256), 0, s, x, part, S, pstride, gain, (bf16_t*)out,\
                        (size_t)D.R64 * D.d, ssq, rm, D.d)
   CERB_S_BUCKET(S, CERB_CALL);
 #undef CERB_CALL
@@ -337,7 +365,7 @@ __device__ __forceinline__ float row_rms_scale(const float* __restrict__ ssq, in
 // attention kernel and k, v into the cache at row L + node.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const double* __restrict__ inv_freq,
+__global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride, const float2* __restrict__ rope_cs,
                           const RowMap rm, T* __restrict__ q, size_t q_lo_off, T* __restrict__ kv_layer,
                           T* __restrict__ ktree, T* __restrict__ vtree, const float* __restrict__ ssq, int nb, const Dims D) {
   const int r = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
@@ -355,10 +383,8 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
   }
 #pragma unroll
   for (int e = 0; e < 6; ++e) v[e] *= rs;
-  // the angle in double: at position ~4000 an fp32 product is already off by 1e-4 rad
-  double snd, csd;
-  sincos((double)rm.row_pos[r] * inv_freq[j], &snd, &csd);
-  const float sn = (float)snd, cs = (float)csd;
+  const float2 rot = rope_cs[(size_t)r * half + j];   // (cos, sin), formed once per step by the embedding kernel
+  const float cs = rot.x, sn = rot.y;
   st_a(q + (size_t)r * d + c0, q_lo_off, v[0] * cs - v[1] * sn);
   st_a(q + (size_t)r * d + c1, q_lo_off, v[0] * sn + v[1] * cs);
   const float k0 = v[2] * cs - v[3] * sn, k1 = v[2] * sn + v[3] * cs;
@@ -381,15 +407,15 @@ __global__ void k_rope_kv(const float* __restrict__ part, int S, size_t pstride,
 }
 
 hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride,
-                          const double* inv_freq, void* q, void* kv_layer, void* ktree, void* vtree, const float* ssq,
+                          const float2* rope_cs, void* q, void* kv_layer, void* ktree, void* vtree, const float* ssq,
                           int rows_max, hipStream_t s) {
   const int nb = add_gain_blocks(D.d);
   dim3 grid(rows_max, D.nH), block(D.dh / 2);
   if (D.dtype == 0)
-    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (float*)q, (size_t)0,
+    hipLaunchKernelGGL((k_rope_kv<float>), grid, block, 0, s, part, S, pstride, rope_cs, rm, (float*)q, (size_t)0,
                        (float*)kv_layer, (float*)nullptr, (float*)nullptr, ssq, nb, D);
   else
-    hipLaunchKernelGGL((k_rope_kv<bf16_t>), grid, block, 0, s, part, S, pstride, inv_freq, rm, (bf16_t*)q,
+    hipLaunchKernelGGL((k_rope_kv<bf16_t>), grid, block, 0, s, part, S, pstride, rope_cs, rm, (bf16_t*)q,
                        (size_t)D.R64 * D.d, (bf16_t*)kv_layer, (bf16_t*)ktree, (bf16_t*)vtree, ssq, nb, D);
   return hipGetLastError();
 }

@@ -723,6 +723,7 @@ def test_graph_replay_equals_eager_launch(tiny_pairs):
     {"gemm_nsub": 4}, {"gemm_target_wgs": 64}, {"gemm_target_wgs": 4096, "gemm_max_split": 16}, {"gemm_max_split": 1},
     {"act_split": 0}, {"act_split": 0, "gemm_nsub": 4, "attn_mfma": 0}, {"attn_chunk": 256}, {"attn_chunk": 128},
     {"gemm_wg_slots": 0}, {"gemm_wg_slots": 40}, {"gemm_uneven_split": 1, "gemm_target_wgs": 100, "gemm_wg_slots": 0},
+    {"gemm_fused": 0}, {"gemm_fused": 1},
 ])
 def test_tiny_tuning_knobs_do_not_change_results(params):
     """Every value of the tuning knobs selects another tiling, split or kernel instance of the same
@@ -794,8 +795,15 @@ def pair_7b():
     return H.Pair("7b", BF16, "p63", seed=0, max_batch=1, kv_capacity=1280, lazy_host=True)
 
 
-def test_7b_full_size_whole_tree_matches_oracle(pair_7b):
-    _full_size_step(pair_7b, 1024, 1280)
+@pytest.mark.parametrize("gemm_fused", [1, 0])
+def test_7b_full_size_whole_tree_matches_oracle(pair_7b, gemm_fused):
+    """The headline configuration, with the whole-K fused QKV / gate-up launches (the default for up to 64
+    rows) and with the split-K GEMMs and separate RoPE / SwiGLU launches."""
+    pair_7b.engine.set_param("gemm_fused", gemm_fused)
+    try:
+        _full_size_step(pair_7b, 1024, 1280)
+    finally:
+        pair_7b.engine.set_param("gemm_fused", 1)
 
 
 def test_7b_120_path_tree_whole_tree_matches_oracle(pair_7b):
