@@ -427,6 +427,7 @@ def main() -> int:
     # dominant kernel: the weight-streaming GEMM.  Every kind is replayed back to back over all
     # layers (fresh weights each launch, so no cache reuse) between two events on this stream.
     gemm = {}
+    fused_on = not any(kv.replace(" ", "") == "gemm_fused=0" for kv in args.param)
     tot_bytes = tot_ms = 0.0
     n_launch = 0
     for kind, kname in enumerate(GEMM_KINDS):
@@ -444,7 +445,12 @@ def main() -> int:
         launches = cfg["n_layers"] if kind <= 3 else (cfg["n_resblocks"] if kind == 5 else 1)
         gemm[kname] = {"ms_per_step": round(ms, 4), "launches": launches, "GB": round(nbytes / 1e9, 4),
                        "GBps": round(nbytes / ms / 1e6, 1), "us_per_launch": round(ms * 1e3 / launches, 2)}
-        if kind <= 4:     # the MT=4 kernel instance (tree rows); head GEMMs run the 16-row instance
+        # the dominant kernel is the split-K GEMM instance for tree rows (O, down, LM head; also QKV and gate/up
+        # where the step does not run those as whole-K fused launches); head GEMMs run the 16-row instance
+        fused_kind = kind in (0, 2) and rows <= 64 and fused_on
+        gemm[kname]["kernel"] = ("k_qkv_rope" if kind == 0 else "k_gate_up_swiglu") if fused_kind else (
+            "k_gemm_bf16<4,2,1>" if kind <= 4 else "k_gemm_bf16<1,2,1>")
+        if kind <= 4 and not fused_kind:
             tot_bytes += nbytes
             tot_ms += ms
             n_launch += launches
@@ -497,7 +503,7 @@ def main() -> int:
         "step_mfma_frac": round(t_mfma / step_s, 4),
         "step_bound": {"hbm_time_at_peak_ms": round(t_hbm * 1e3, 3), "mfma_time_at_peak_ms": round(t_mfma * 1e3, 3),
                        "binding": "hbm" if t_hbm >= t_mfma else "mfma", "rows": rows_step, "sum_prefix": int(sum(Ls))},
-        "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2> (QKV, O, gate/up, down, LM head)",
+        "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2,1> (" + ", ".join(k for k, v in gemm.items() if v["kernel"] == "k_gemm_bf16<4,2,1>") + ")",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 and Bn == 1 and T == 64 and not args.ar else None),

@@ -217,7 +217,9 @@ int cerberus_set_param(cerberus_ctx *ctx, const char *name, int32_t value);
 /* Benchmark hook: enqueues back to back, for every layer (or head stage), the GEMM launches of
  * one kind exactly as a step launches them for `rows` rows, reading whatever the activation
  * buffers hold; results land in scratch.  kind: 0 QKV, 1 attention output, 2 FFN gate/up,
- * 3 FFN down, 4 LM head, 5 head Resblocks (all stages), 6 head FC.  Writes to *bytes (HOST, may
+ * 3 FFN down, 4 LM head, 5 head Resblocks (all stages), 6 head FC.  Where a step of `rows` rows runs the
+ * QKV or gate/up projection as a whole-K fused launch, so does the hook (over the rows of the last
+ * step's row map, which must have had that many; without the cache write).  Writes to *bytes (HOST, may
  * be NULL) the weight + activation bytes the launches read once each.                          */
 int cerberus_bench_gemm(cerberus_ctx *ctx, int32_t kind, int32_t rows, void *stream, double *bytes);
 

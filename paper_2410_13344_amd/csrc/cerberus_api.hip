@@ -464,6 +464,27 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
     if (rc_ != CERBERUS_OK) return rc_; \
   } while (0)
 
+// whole-K fused launches of layer l over the rows of the current row map (kv_layer may be null: no cache write)
+int run_fused_qkv(const cerberus_ctx* c, int l, void* kv_layer, hipStream_t s) {
+  const Dims& D = c->D;
+  FusedQkvArgs fa{};
+  fa.W = c->wqkv[l]; fa.At = c->xn; fa.slabs = c->slabs_qkv; fa.ksteps = kpad(c->cfg, D.d) / 32; fa.ssq = c->ssq;
+  fa.nb = add_gain_blocks(D.d); fa.rope_cs = c->rope_cs; fa.rm = c->rm; fa.q = (bf16_t*)c->q; fa.kv_layer = (bf16_t*)kv_layer;
+  fa.ktree = (bf16_t*)c->ktree; fa.vtree = (bf16_t*)c->vtree; fa.lo_off = (size_t)c->R64 * D.d; fa.D = D;
+  HIP_TRY(launch_qkv_rope(fa, c->ns_qkv, c->fused_grid, s));
+  return CERBERUS_OK;
+}
+
+int run_fused_gate_up(const cerberus_ctx* c, int l, hipStream_t s) {
+  const Dims& D = c->D;
+  FusedGateUpArgs ga{};
+  ga.W = c->wgu[l]; ga.At = c->xn; ga.slabs = c->slabs_gu; ga.ksteps = kpad(c->cfg, D.d) / 32; ga.ssq = c->ssq;
+  ga.nb = add_gain_blocks(D.d); ga.d = D.d; ga.eps = D.eps; ga.rm = c->rm; ga.act = (bf16_t*)c->act;
+  ga.lo_off = (size_t)c->R64 * D.Fpad; ga.Fpad = D.Fpad;
+  HIP_TRY(launch_gate_up_swiglu(ga, c->ns_gu, c->fused_grid, s));
+  return CERBERUS_OK;
+}
+
 // Embedding, the decoder layers and, with `head`, final norm + LM head + per-row argmax, over the
 // rows the assembly kernel laid out; `tr` supplies the attention mask (candidate tree, or a chain).
 int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_max, const TreeDev& tr, bool head,
@@ -478,18 +499,13 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
   // launches of up to 64 rows: QKV + RoPE + KV write and gate/up + SwiGLU as one whole-K launch each
   const bool fused = c->use_fused && D.dtype == CERBERUS_BF16 && rows_max <= 64 && c->fused_grid > 0 && c->act_split == 1;
   const bool fq = fused && c->ns_qkv > 0, fg = fused && c->ns_gu > 0;
-  const int nb = add_gain_blocks(D.d);
   for (int l = 0; l < D.n_layers; ++l) {
     HIP_TRY(launch_add_gain(D, rm, c->x, prev ? prev->out : nullptr, prev ? prev->S : 0,
                             prev ? (size_t)prev->out_rows * prev->N : 0, c->attn_norm[l], c->xn, c->ssq, rows_max, s, fq));
     GemmProb pq, po, pg;
     void* kv_layer = (unsigned char*)st->kv + (size_t)l * kv_layer_bytes;
     if (fq) {
-      FusedQkvArgs fa{};
-      fa.W = c->wqkv[l]; fa.At = c->xn; fa.slabs = c->slabs_qkv; fa.ksteps = kpad(c->cfg, D.d) / 32; fa.ssq = c->ssq; fa.nb = nb;
-      fa.rope_cs = c->rope_cs; fa.rm = rm; fa.q = (bf16_t*)c->q; fa.kv_layer = (bf16_t*)kv_layer; fa.ktree = (bf16_t*)c->ktree;
-      fa.vtree = (bf16_t*)c->vtree; fa.lo_off = (size_t)c->R64 * D.d; fa.D = D;
-      HIP_TRY(launch_qkv_rope(fa, c->ns_qkv, c->fused_grid, s));
+      TRY(run_fused_qkv(c, l, kv_layer, s));
     } else {
       TRY(run_gemm(c, c->p_qkv[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pq));
       HIP_TRY(launch_rope_kv(D, rm, pq.out, pq.S, (size_t)pq.out_rows * pq.N, c->rope_cs, c->q, kv_layer, c->ktree, c->vtree,
@@ -504,10 +520,7 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &po));
     HIP_TRY(launch_add_gain(D, rm, c->x, po.out, po.S, (size_t)po.out_rows * po.N, c->ffn_norm[l], c->xn, c->ssq, rows_max, s, fg));
     if (fg) {
-      FusedGateUpArgs ga{};
-      ga.W = c->wgu[l]; ga.At = c->xn; ga.slabs = c->slabs_gu; ga.ksteps = kpad(c->cfg, D.d) / 32; ga.ssq = c->ssq; ga.nb = nb;
-      ga.d = D.d; ga.eps = D.eps; ga.rm = rm; ga.act = (bf16_t*)c->act; ga.lo_off = (size_t)c->R64 * D.Fpad; ga.Fpad = D.Fpad;
-      HIP_TRY(launch_gate_up_swiglu(ga, c->ns_gu, c->fused_grid, s));
+      TRY(run_fused_gate_up(c, l, s));
     } else {
       TRY(run_gemm(c, c->p_gu[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &pg));
       HIP_TRY(launch_swiglu(D, rm, pg.out, pg.S, (size_t)pg.out_rows * pg.N, c->act, c->ssq, rows_max, s));
@@ -847,7 +860,16 @@ int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* str
     GemmProb launched;   // layer and LM-head launches choose their split by row count, as in a step
     return run_gemm(ctx, g, nullptr, rows, rows, nullptr, 0, s, head_kind ? nullptr : &launched);
   };
-  if (kind <= 3) {
+  const bool fused = ctx->use_fused && D.dtype == CERBERUS_BF16 && rows <= 64 && ctx->fused_grid > 0 && ctx->act_split == 1;
+  if (kind == 0 && fused && ctx->ns_qkv) {
+    // what a step of this many rows launches for the QKV projection: the whole-K kernel with its RoPE
+    // epilogue, over the rows of the last step's row map (which must hold `rows` rows), minus the cache write
+    for (int l = 0; l < D.n_layers; ++l) TRY(run_fused_qkv(ctx, l, nullptr, s));
+    total = (double)D.n_layers * ((double)3 * D.d * D.d + (double)rows * D.d * 2) * ctx->elem;
+  } else if (kind == 2 && fused && ctx->ns_gu) {
+    for (int l = 0; l < D.n_layers; ++l) TRY(run_fused_gate_up(ctx, l, s));
+    total = (double)D.n_layers * ((double)2 * D.F * D.d + (double)rows * D.d * 2) * ctx->elem;
+  } else if (kind <= 3) {
     const std::vector<GemmBatch>& v = kind == 0 ? ctx->p_qkv : kind == 1 ? ctx->p_o : kind == 2 ? ctx->p_gu : ctx->p_down;
     for (int l = 0; l < D.n_layers; ++l) TRY(run(v[l]));
   } else if (kind == 4) {

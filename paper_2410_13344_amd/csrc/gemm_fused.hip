@@ -201,9 +201,11 @@ __global__ __launch_bounds__(kWaves * 64) void k_qkv_rope(const FusedQkvArgs a) 
           st_a(a.q + (size_t)r * d + c0, a.lo_off, y0);
           st_a(a.q + (size_t)r * d + c1, a.lo_off, y1);
         } else {
-          bf16_t* Kr = a.kv_layer + (((size_t)(0 * D.Bmax + b) * D.nH + h) * D.cap + cache_row[k]) * dh;
-          Kr[j] = f32_to_bf16(y0);
-          Kr[j + half] = f32_to_bf16(y1);
+          if (a.kv_layer) {   // (the benchmark hook has no cache to write to)
+            bf16_t* Kr = a.kv_layer + (((size_t)(0 * D.Bmax + b) * D.nH + h) * D.cap + cache_row[k]) * dh;
+            Kr[j] = f32_to_bf16(y0);
+            Kr[j + half] = f32_to_bf16(y1);
+          }
           st_a(a.ktree + (size_t)r * d + c0, a.lo_off, y0);
           st_a(a.ktree + (size_t)r * d + c1, a.lo_off, y1);
         }
@@ -214,8 +216,10 @@ __global__ __launch_bounds__(kWaves * 64) void k_qkv_rope(const FusedQkvArgs a) 
           if (sv < 0) continue;
           const int col = (sv % spd) * 16 + c, h = col / dh, j = col % dh;
           const float y = pair_sum(red, which, e) * scale;
-          bf16_t* Vr = a.kv_layer + (((size_t)(1 * D.Bmax + b) * D.nH + h) * D.cap + cache_row[k]) * dh;
-          Vr[j] = f32_to_bf16(y);
+          if (a.kv_layer) {
+            bf16_t* Vr = a.kv_layer + (((size_t)(1 * D.Bmax + b) * D.nH + h) * D.cap + cache_row[k]) * dh;
+            Vr[j] = f32_to_bf16(y);
+          }
           st_a(a.vtree + (size_t)r * d + col, a.lo_off, y);
         }
       }
