@@ -204,6 +204,8 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  *                                              fills >= 90 % of them in one round is preferred; 0 = off
  *   "gemm_uneven_split" (0 or 1, default 0)    1: take the split the target gives even if it does not divide K
  *   "gemm_nsub"       (2 or 4, default 2)      16-column slabs per wave (64*nsub columns per workgroup)
+ *   "gemm_nsub_rows"  (2 or 4, default 2)      the same for launches of more than 64 rows (several row blocks);
+ *                                              4 runs one workgroup per CU with the whole register file
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)
  *   "attn_chunk"      (128 or 256, default 128) committed cache rows per attention workgroup

@@ -83,7 +83,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0, prompt_rows = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, act_split = 1, attn_chunk = 128, uneven_split = 0, wg_slots = 512;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 2, act_split = 1, attn_chunk = 128, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
 
@@ -446,6 +446,7 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
   // plans are made for 17..64 rows; other row counts run other kernel instances or several row
   // blocks and get their own split (only where the caller takes the launched description back)
   if (launched && (rows_max > 64 || rows_max <= 16)) {
+    if (rows_max > 64) g.nsub = c->gemm_nsub_rows;   // several row blocks: 2 slabs per wave, or the 4-slab one-workgroup-per-CU instance (measured no faster)
     for (int p = 0; p < g.n_prob; ++p) g.p[p].out_rows = (int)align_up((size_t)rows_max, 64);   // partials packed for this launch
     split_plan(c, g, rows_max);
   }
@@ -915,6 +916,9 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
     if (value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub must be 2 or 4");
     ctx->gemm_nsub = value;
     build_plans(ctx);
+  } else if (n == "gemm_nsub_rows") {
+    if (value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub_rows must be 2 or 4");
+    ctx->gemm_nsub_rows = value;
   } else if (n == "act_split") {
     if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "act_split must be 0 or 1");
     ctx->act_split = value;

@@ -47,6 +47,9 @@ hipError_t launch_pack_weight(const bf16_t* W, void* packed, int N, int K, int K
 // loads stay in flight across chunk boundaries.
 // ---------------------------------------------------------------------------------------------
 constexpr int kLdsRow = 512;
+#ifndef CERB_ROWS_RING
+#define CERB_ROWS_RING 8
+#endif
 #ifndef CERB_KRING
 #define CERB_KRING 8
 #endif
@@ -61,7 +64,7 @@ __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
 }
 
 template <int MT, int NSUB, int SPLIT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_gemm_bf16(const GemmBatch g) {
+__device__ __forceinline__ void gemm_bf16_body(const GemmBatch& g) {
   if (gemm_skip(g)) return;
   const int rows = g.n_rows ? *g.n_rows : g.rows_static;
   // One-dimensional grid, numbered so that the row blocks of one (column tile, split) have ids 8
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int split = local % P.S;
   const int ntile = local / P.S;
   constexpr int KSC = SPLIT ? 4 : 8;         // k-steps per LDS chunk
-  constexpr int kRing = SPLIT ? kRingSplit : kRingSplit / 2;
+  constexpr int kRing = (MT == 4 && NSUB == 4) ? CERB_ROWS_RING : SPLIT ? kRingSplit : kRingSplit / 2;
   static_assert((2 * KSC) % kRing == 0 && (kRing % KSC == 0 || KSC % kRing == 0),
                 "ring slots must be compile-time constants: k-step (chunk parity * KSC + s) lives in slot of that index mod kRing");
   const int ksteps = P.K / 32;               // K is a multiple of 256
@@ -161,9 +164,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   CERB_A_LD(P, 0, 0)
   uint4 ring[kRing][NSUB];
 #pragma unroll
-  for (int i = 0; i < kRing; ++i)
+  for (int i = 0; i < kRing; ++i)     // slot kRing - 1 is filled by the first k-step of the loop (its load below is not waited for)
 #pragma unroll
-    for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + i, ks1 - 1) * 64];
+    for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + min(i, kRing - 2), ks1 - 1) * 64];
   CERB_A_ST(P, 0, 0)
   CERB_A_LD(P, min(1, nchunks - 1), 0)
   __syncthreads();
@@ -173,14 +176,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #define CERB_GEMM_CHUNK(C, PAR, NEXT2, NEXT1, FULL)                                                                                \
   {                                                                                                                       \
     CERB_A_LD(NEXT2, min((C) + 2, nchunks - 1), FULL)                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                                                    \
     const unsigned char* L = lds + ((C) & 1) * kBuf + a_row * kLdsRow;                                                    \
     const int kb = ks0 + (C) * KSC;                                                                                       \
     _Pragma("unroll") for (int s = 0; s < KSC; ++s) {                                                                     \
-      uint4 b[NSUB];                                                                                                      \
-      _Pragma("unroll") for (int j = 0; j < NSUB; ++j) {                                                                  \
-        b[j] = ring[((PAR) * KSC + s) % kRing][j];                                                                        \
-        ring[((PAR) * KSC + s) % kRing][j] = wp[j][(size_t)min(kb + s + kRing, ks1 - 1) * 64];                            \
-      }                                                                                                                   \
+      /* The slot multiplied in the previous k-step takes the load for kRing - 1 k-steps ahead; this k-step's slot */       \
+      /* is read in place.  (Refilling the slot being read needs a copy of it first, and the copies of a whole     */       \
+      /* chunk get hoisted to its top, where they wait for every load in flight.)  The scheduling barrier keeps   */       \
+      /* the load here instead of wherever the scheduler would sink it.                                           */       \
+      _Pragma("unroll") for (int j = 0; j < NSUB; ++j)                                                                    \
+        ring[((PAR) * KSC + s + kRing - 1) % kRing][j] = wp[j][(size_t)min(kb + s + kRing - 1, ks1 - 1) * 64];            \
+      __builtin_amdgcn_sched_barrier(0);                                                                                  \
+      const uint4* b = ring[((PAR) * KSC + s) % kRing];                                                                   \
       _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) if (FULL || mt < mt_n) {                                                  \
         const uint4 a = *reinterpret_cast<const uint4*>(L + mt * 16 * kLdsRow + (((s * 4 + a_grp) ^ a_row) * 16));        \
         _Pragma("unroll") for (int j = 0; j < NSUB; ++j) acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(            \
@@ -233,6 +240,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   }
 }
 
+// Two workgroups per CU: the weight-streaming instances, whose time goes to loads in flight.
+template <int MT, int NSUB, int SPLIT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_gemm_bf16(const GemmBatch g) {
+  gemm_bf16_body<MT, NSUB, SPLIT>(g);
+}
+
+// One workgroup per CU with the whole register file: 64 rows x 4 slabs per wave.  Launches of several
+// row blocks are bound by MFMA issue and by the LDS reads of the activation fragments; a fragment read
+// once serves four slabs here instead of two.
+template <int SPLIT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_rows(const GemmBatch g) {
+  gemm_bf16_body<4, 4, SPLIT>(g);
+}
+
 // ---------------------------------------------------------------------------------------------
 // fp32 reference-mode GEMM (small models only): one thread per output column, 4 rows per block
 // pass, plain sequential fp32 accumulation.  Workgroup = 64 columns x 16 rows.
@@ -262,7 +283,10 @@ int gemm_cols_per_wg(int dtype, int nsub) { return dtype == 0 ? 64 : 64 * nsub; 
 
 template <int MT>
 static void launch_bf16(const GemmBatch& g, dim3 grid, hipStream_t s) {
-  if (g.nsub == 4) {
+  if (MT == 4 && g.nsub == 4) {
+    if (g.split) hipLaunchKernelGGL((k_gemm_bf16_rows<1>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf16_rows<0>), grid, dim3(256), 0, s, g);
+  } else if (g.nsub == 4) {
     if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 1>), grid, dim3(256), 0, s, g);
     else hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 0>), grid, dim3(256), 0, s, g);
   } else {
