@@ -204,11 +204,14 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  *                                              fills >= 90 % of them in one round is preferred; 0 = off
  *   "gemm_uneven_split" (0 or 1, default 0)    1: take the split the target gives even if it does not divide K
  *   "gemm_nsub"       (2 or 4, default 2)      16-column slabs per wave (64*nsub columns per workgroup)
- *   "gemm_nsub_rows"  (2 or 4, default 2)      the same for launches of more than 64 rows (several row blocks);
- *                                              4 runs one workgroup per CU with the whole register file
+ *   "gemm_nsub_rows"  (0, 2 or 4, default 0)   the same for launches of more than 64 rows (several row blocks);
+ *                                              4 runs one workgroup per CU with the whole register file; 0 picks
+ *                                              4 for the down projection and the LM head past 256 rows, else 2
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)
- *   "attn_chunk"      (128 or 256, default 128) committed cache rows per attention workgroup
+ *   "attn_chunk"      (128 or 256, default 128) committed cache rows per round of an attention workgroup
+ *   "attn_target_wgs" (1..65536, default 1024) workgroups the attention work list aims at (over all heads): the
+ *                                              longer the sequences, the more rounds a workgroup walks
  *   "attn_mfma"       (0 or 1, default 1)      0: plain attention kernel instead of the MFMA one
  *   "gemm_fused"      (0 or 1, default 1)      1: bf16 launches of up to 64 rows run QKV + RoPE + KV write and
  *                                              gate/up + SwiGLU as one whole-K launch each (where the shapes

@@ -83,7 +83,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0, prompt_rows = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 2, act_split = 1, attn_chunk = 128, uneven_split = 0, wg_slots = 512;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
 
@@ -206,6 +206,8 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
   c->rm.row_node = b.take<int>(Rmax);
   c->rm.row_pos = b.take<int>(Rmax);
   c->rm.row_tok = b.take<int>(Rmax);
+  c->rm.att_item = b.take<int4>((size_t)B * c->n_chunks_max);
+  c->rm.seq_npi = b.take<int>(B);
   c->last_row = b.take<int>(B);
   c->path = b.take<int>((size_t)B * (D.Hc + 1));
   c->topk_v = b.take<float>((size_t)D.Hc * B * TOPK_MAX_PARTS * CERBERUS_MAX_TOPK);
@@ -404,9 +406,9 @@ void build_plans(cerberus_ctx* c) {
     { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, 64, false); }
     { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wo[l], &N, &K, 64, false); }
     { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, 64, false); }
-    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, 64, false); }
+    { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, 64, false); c->p_down[l].wide_rows = 1; }
   }
-  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, 64, false); }
+  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, 64, false); c->p_lm.wide_rows = 1; }
   c->p_res.resize(D.R);
   const void* A[CERBERUS_MAX_HEADS]; const void* W[CERBERUS_MAX_HEADS];
   int lda[CERBERUS_MAX_HEADS], N[CERBERUS_MAX_HEADS], K[CERBERUS_MAX_HEADS];
@@ -446,7 +448,10 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
   // plans are made for 17..64 rows; other row counts run other kernel instances or several row
   // blocks and get their own split (only where the caller takes the launched description back)
   if (launched && (rows_max > 64 || rows_max <= 16)) {
-    if (rows_max > 64) g.nsub = c->gemm_nsub_rows;   // several row blocks: 2 slabs per wave, or the 4-slab one-workgroup-per-CU instance (measured no faster)
+    // several row blocks: 2 slabs per wave, or the 4-slab one-workgroup-per-CU instance.  Measured at the 7B
+    // shapes: the 4-slab instance wins only past 256 rows and only where the planner marked the problem
+    // (long K against few columns, or the vocabulary-wide LM head); the knob forces either one.
+    if (rows_max > 64) g.nsub = c->gemm_nsub_rows ? c->gemm_nsub_rows : (rows_max > 256 && plan.wide_rows) ? 4 : 2;
     for (int p = 0; p < g.n_prob; ++p) g.p[p].out_rows = (int)align_up((size_t)rows_max, 64);   // partials packed for this launch
     split_plan(c, g, rows_max);
   }
@@ -516,6 +521,10 @@ int forward_rows(cerberus_ctx* c, const cerberus_state* st, int batch, int rows_
     aa.q = c->q; aa.q_lo_off = D.dtype == CERBERUS_BF16 ? (size_t)c->R64 * D.d : 0; aa.kv = kv_layer; aa.ktree = c->ktree; aa.vtree = c->vtree; aa.out = c->attn; aa.out_lo_off = (size_t)c->R64 * D.d; aa.part_o = c->attn_po; aa.part_ml = c->attn_ml; aa.rm = rm;
     aa.anc = tr.anc; aa.aw = tr.aw; aa.Tpad = (int)align_up((size_t)tr.T, 64); aa.tc_max = ceil_div(tr.T, 64); aa.batch = batch; aa.Bmax = D.Bmax; aa.nH = D.nH; aa.dh = D.dh; aa.cap = D.cap; aa.T = tr.T;
     aa.chunk = c->attn_chunk; aa.n_chunks_max = ceil_div(D.cap, c->attn_chunk) + aa.tc_max;   // <= c->n_chunks_max, which sized the partial buffers
+    // every item gets a workgroup per head: at most target / nH cache-range items plus one per sequence from
+    // rounding, and the tree chunks
+    aa.att_cap = D.Bmax * c->n_chunks_max;
+    aa.grid_x = std::min(batch * aa.n_chunks_max, std::max(1, c->attn_target_wgs / D.nH) + batch * (1 + aa.tc_max));
     aa.rows_max = rows_max; aa.status = st->status;
     HIP_TRY(launch_attention(aa, D.dtype, c->use_mfma_attn, s));
     TRY(run_gemm(c, c->p_o[l], rm.n_rows, 0, rows_max, nullptr, 0, s, &po));
@@ -570,6 +579,12 @@ int run_heads(cerberus_ctx* c, const cerberus_state* st, int batch, hipStream_t 
   return CERBERUS_OK;
 }
 
+// the attention work list is built only for the MFMA kernel; the plain one walks rows and heads
+AttnPlanCfg attn_plan_cfg(const cerberus_ctx* c) {
+  const bool mfma = c->cfg.dtype == CERBERUS_BF16 && c->use_mfma_attn;
+  return AttnPlanCfg{mfma ? c->attn_chunk : 0, c->attn_target_wgs, c->D.Bmax * c->n_chunks_max};
+}
+
 int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream, int mode) {
   TRY(check_state(c, st, batch));
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -577,7 +592,7 @@ int run_step(cerberus_ctx* c, const cerberus_state* st, int batch, void* stream,
   const RowMap& rm = c->rm;
   const int rows_max = (mode == ASSEMBLE_FORCE_AR) ? batch : batch * D.T;
 
-  HIP_TRY(launch_assemble(D, c->tree, rm, *st, c->taps, batch, mode, PromptArgs{}, s));
+  HIP_TRY(launch_assemble(D, c->tree, rm, *st, c->taps, batch, mode, PromptArgs{}, attn_plan_cfg(c), s));
   TRY(forward_rows(c, st, batch, rows_max, c->tree, true, s));
 
   HIP_TRY(launch_accept(D, c->tree, rm, c->g, rm.row_tok, *st, c->path, c->last_row, batch, s));
@@ -602,7 +617,7 @@ int run_prompt(cerberus_ctx* c, const cerberus_state* st, int batch, int seq, co
   for (int off = 0; off < n_tokens; off += c->chain.T) {
     const int n = std::min(c->chain.T, n_tokens - off);
     const bool last = off + n >= n_tokens;
-    HIP_TRY(launch_assemble(D, c->chain, rm, *st, c->taps, batch, ASSEMBLE_PROMPT, PromptArgs{tokens + off, n, seq}, s));
+    HIP_TRY(launch_assemble(D, c->chain, rm, *st, c->taps, batch, ASSEMBLE_PROMPT, PromptArgs{tokens + off, n, seq}, attn_plan_cfg(c), s));
     TRY(forward_rows(c, st, batch, n, c->chain, last, s));
     HIP_TRY(launch_prompt_commit(rm, *st, c->g, c->last_row, batch, seq, last ? 1 : 0, s));
     if (last) {
@@ -807,7 +822,7 @@ int cerberus_accept(cerberus_ctx* ctx, const int32_t* node_argmax, const int32_t
   if (!node_argmax || !node_token) return fail(CERBERUS_ERR_ARG, "null node arrays");
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   cerberus_taps none{};
-  HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, s));
+  HIP_TRY(launch_assemble(ctx->D, ctx->tree, ctx->rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, AttnPlanCfg{0, 0, 0}, s));
   HIP_TRY(launch_accept(ctx->D, ctx->tree, ctx->rm, node_argmax, node_token, *st, ctx->path, ctx->last_row, batch, s));
   HIP_TRY(launch_compact(ctx->D, ctx->rm, *st, ctx->path, batch, s));
   return CERBERUS_OK;
@@ -841,7 +856,7 @@ int cerberus_accept_noalloc(cerberus_ctx* ctx, const int32_t* node_argmax, const
   cerberus_taps none{};
   // every word the three kernels read from the array is written by an earlier one of them in this call
   // (the assembly writes the map of all `batch` sequences), so nothing has to start at zero
-  HIP_TRY(launch_assemble(D, ctx->tree, rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, s));
+  HIP_TRY(launch_assemble(D, ctx->tree, rm, *st, none, batch, ASSEMBLE_FULL_TREE, PromptArgs{}, AttnPlanCfg{0, 0, 0}, s));
   HIP_TRY(launch_accept(D, ctx->tree, rm, node_argmax, node_token, *st, path, last_row, batch, s));
   HIP_TRY(launch_compact(D, rm, *st, path, batch, s));
   return CERBERUS_OK;
@@ -916,8 +931,11 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
     if (value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub must be 2 or 4");
     ctx->gemm_nsub = value;
     build_plans(ctx);
+  } else if (n == "attn_target_wgs") {
+    if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "attn_target_wgs out of 1..65536");
+    ctx->attn_target_wgs = value;
   } else if (n == "gemm_nsub_rows") {
-    if (value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub_rows must be 2 or 4");
+    if (value != 0 && value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub_rows must be 0, 2 or 4");
     ctx->gemm_nsub_rows = value;
   } else if (n == "act_split") {
     if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "act_split must be 0 or 1");

@@ -47,6 +47,18 @@ struct RowMap {
   int* row_node;  // [Rmax]
   int* row_pos;   // [Rmax]
   int* row_tok;   // [Rmax]
+  // work list of the MFMA attention kernel, written with the row map (null where no attention follows)
+  int4* att_item; // [att_cap] x = (sequence << 16) | index j of the item within its sequence (first the sequence's
+                  // cache-range items, then its tree chunks), y = kv_len, z = (rows of the sequence << 16) | its
+                  // first row, w = (cache-range items of the sequence << 16) | chunks per cache-range item;
+                  // x = -1 from the end of the list on
+  int* seq_npi;   // [B] cache-range items of the sequence
+};
+
+struct AttnPlanCfg {
+  int chunk;       // committed cache rows per chunk: cache-range items are cut in these units (0: no work list)
+  int target_wgs;  // the work list aims at this many workgroups over all heads
+  int att_cap;     // entries of the list
 };
 
 struct TreeDev {
@@ -88,6 +100,7 @@ struct GemmBatch {
   int split;                     // bf16: 1 = multiply the hi and the lo activation plane, 0 = hi only
   int row_blocks;                // bf16: blocks of 64 rows in the launch (set by the launcher)
   int fixed_s1;                  // host side: the planner keeps split-K off (the consumer reads out[0] as the result)
+  int wide_rows;                 // host side: launches of more than 256 rows take the 4-slab instance (down projection, LM head)
 };
 
 // launchers (defined next to their kernels)
@@ -103,7 +116,7 @@ struct AttnArgs {
   const void* vtree; //            the tree keys are read from here, the cache only serves rows < L
   void* out;         // [rows][nH*dh] attention output (GEMM A operand; bf16: lo plane out_lo_off elements later)
   size_t out_lo_off;
-  float* part_o;     // [B][nH][n_chunks_max][Tpad][dh]; slots ceil(L/128).. of a (seq, head) hold the tree chunks
+  float* part_o;     // [B][nH][n_chunks_max][Tpad][dh]; slot j of a (seq, head) belongs to the sequence's work item j
   float* part_ml;    // [B][nH][n_chunks_max][Tpad][2]
   RowMap rm;
   const unsigned long long* anc;   // [T][aw]
@@ -111,8 +124,10 @@ struct AttnArgs {
   int Tpad;          // tree size rounded up to 64: query rows per partial slot
   int tc_max;        // tree chunks (64 of this step's rows each) at the end of the chunk grid, ceil(T / 64)
   int batch, Bmax, nH, dh, cap, T;
-  int chunk;         // keys per workgroup
+  int chunk;         // committed cache rows per chunk of the work list
   int n_chunks_max;
+  int grid_x;        // workgroups along the item axis (the kernel strides over the list if it is longer)
+  int att_cap;       // entries of the work list
   int rows_max;
   int* status;
 };

@@ -36,7 +36,7 @@ struct TopkArgs {
 };
 
 hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, const cerberus_state& st,
-                           const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, hipStream_t s);
+                           const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, const AttnPlanCfg& ap, hipStream_t s);
 hipError_t launch_prompt_commit(const RowMap& rm, const cerberus_state& st, const int* g, int* last_row, int batch, int seq,
                                 int last_pass, hipStream_t s);
 // also fills rope_cs[row][j] = (cos, sin)(pos(row) * inv_freq[j]), j < dh/2, the angle formed in double

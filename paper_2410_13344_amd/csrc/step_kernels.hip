@@ -100,7 +100,8 @@ __device__ __forceinline__ float4 add_parts(float4 a, const Parts<MAXS, float4>&
 // has, and the token / position of each.  One block; sequences pack their rows back to back.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr, const RowMap rm, const cerberus_state st,
-                                                 const cerberus_taps tp, int batch, int mode, const PromptArgs pa) {
+                                                 const cerberus_taps tp, int batch, int mode, const PromptArgs pa,
+                                                 const AttnPlanCfg ap) {
   __shared__ int sT[CERBERUS_MAX_BATCH], sL[CERBERUS_MAX_BATCH], sRow0[CERBERUS_MAX_BATCH];
   const int t = threadIdx.x;
   if (t < batch) {
@@ -127,6 +128,29 @@ __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr,
     *rm.n_rows = mode == ASSEMBLE_FULL_TREE ? batch * tr.T : r;
   }
   __syncthreads();
+  if (rm.att_item != nullptr && ap.chunk > 0) {
+    // Work list of the attention kernel, sized by the lengths the sequences have now, not by the cache
+    // capacity: a cache-range item covers `cps` chunks of one sequence's committed rows, a tree item 64 of
+    // the step's own rows.  cps grows with the total length so that the list stays near the workgroup
+    // target: a long cache is walked inside a workgroup (one partial result per item) instead of being cut
+    // into a partial per chunk.  Every thread derives the same plan; thread i writes entries i, i + 64, ...
+    int chunks = 0;
+    for (int b = 0; b < batch; ++b)
+      if (sT[b] > 0) chunks += (sL[b] + ap.chunk - 1) / ap.chunk;
+    const int per_head = max(1, ap.target_wgs / D.nH);
+    const int cps = min(0xffff, max(1, (chunks + per_head - 1) / per_head));
+    int n = 0;
+    for (int b = 0; b < batch; ++b) {
+      const int npi = sT[b] > 0 ? ((sL[b] + ap.chunk - 1) / ap.chunk + cps - 1) / cps : 0;
+      const int ntree = (sT[b] + 63) / 64;
+      if (t == 0) rm.seq_npi[b] = npi;
+      for (int j = t; j < npi + ntree; j += blockDim.x)
+        if (n + j < ap.att_cap) rm.att_item[n + j] = make_int4((b << 16) | j, sL[b], (sT[b] << 16) | sRow0[b], (npi << 16) | cps);
+      n += npi + ntree;
+    }
+    for (int i = n + t; i < ap.att_cap; i += blockDim.x) rm.att_item[i] = make_int4(-1, 0, 0, 0);
+  }
+  __syncthreads();
   if (t < batch) { rm.seq_T[t] = sT[t]; rm.seq_L[t] = sL[t]; rm.seq_row0[t] = sRow0[t]; }
   for (int b = 0; b < batch; ++b) {
     for (int node = t; node < sT[b]; node += blockDim.x) {
@@ -148,8 +172,8 @@ __global__ __launch_bounds__(64) void k_assemble(const Dims D, const TreeDev tr,
 }
 
 hipError_t launch_assemble(const Dims& D, const TreeDev& tr, const RowMap& rm, const cerberus_state& st,
-                           const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, hipStream_t s) {
-  hipLaunchKernelGGL(k_assemble, dim3(1), dim3(64), 0, s, D, tr, rm, st, tp, batch, mode, pa);
+                           const cerberus_taps& tp, int batch, int mode, const PromptArgs& pa, const AttnPlanCfg& ap, hipStream_t s) {
+  hipLaunchKernelGGL(k_assemble, dim3(1), dim3(64), 0, s, D, tr, rm, st, tp, batch, mode, pa, ap);
   return hipGetLastError();
 }
 

@@ -584,6 +584,37 @@ def test_tiny_batch_mixed_ar_and_tree_in_one_launch(dtype):
         assert out["T"] == 1 and not rep.failures, f"ar seq {b}: " + "; ".join(rep.failures)
 
 
+@pytest.mark.parametrize("target_wgs,chunk", [(1, 128), (8, 128), (16, 128), (4096, 128), (1, 256), (4096, 256)])
+def test_tiny_attention_work_list(target_wgs, chunk):
+    """The MFMA attention kernel walks a work list built from the sequences' present lengths: with a small
+    workgroup target a cache range of several chunks is one item (running softmax over its rounds, the last
+    round ragged), with a large one every chunk is its own item; three sequences of different lengths, one
+    of them on the one-token path, share the launch.  Either way the step matches the oracle."""
+    pair = H.Pair("tiny", BF16, "p63", seed=0, max_batch=3, kv_capacity=640, topk=6)
+    pair.engine.set_param("attn_chunk", chunk)
+    pair.engine.set_param("attn_target_wgs", target_wgs)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    osts = []
+    for b, (n_prompt, flag) in enumerate(((531, 0), (300, 1), (129, 0))):     # 5, 3 and 2 chunks of 128 rows
+        prompt = synth.make_token_ids(n_prompt, cfg["vocab"], seed=60 + b).numpy()
+        ost = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+        ost["flag"] = flag
+        H.round_oracle_kv(ost, BF16)
+        H.upload_sequence(st, b, ost, BF16)
+        osts.append(ost)
+    outs = [pair.oracle_step(ost) for ost in osts]
+    pair.engine.verify_step(st, 3)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    for b, (ost, out) in enumerate(zip(osts, outs)):
+        rep = H.compare_step(cfg, out, st, taps, b, pair.T, BF16, ost, tol=H.TOL_BF16_TINY)
+        say(f"  target {target_wgs} chunk {chunk} seq {b}: L={out['L_before']} logit_err={rep.max_logit_err:.2e}")
+        assert not rep.failures, f"seq {b}: " + "; ".join(rep.failures)
+    pair.engine.close()
+
+
 @pytest.mark.parametrize("tree", ["root", "chain4", "rand17s1k4", "rand33s2k4", "rand65s3k4", "rand100s4k4", "rand129s5k4"])
 def test_tiny_odd_tree_shapes(tree):
     """Tree sizes that are no multiple of anything (a lone root, a single chain, random shapes around
