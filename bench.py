@@ -148,15 +148,15 @@ def cpu_baseline_schedule(cfg, W_dev, parent, rank, kv_t, L, root, cand, n_tree,
             "measured_s": round(sum(tt) + sum(ta), 3)}
 
 
-def profiled_traffic_mb():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy), or None when no summary is there."""
+def profiled_traffic_mb(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of the default workload
+    (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy), or None when the summary has no line for it."""
     path = os.path.join(ROOT, "profiles", "verify_step_7b_t64_l1024.txt")
     try:
         for line in open(path):
-            if line.startswith("average over all launches: fetch"):
-                parts = line.split()
-                return float(parts[5]) + float(parts[8])
+            if line.startswith(f"traffic {kernel}:"):
+                parts = line.split(":", 1)[1].split()
+                return round(float(parts[1]) + float(parts[4]), 1)       # "fetch X MB, write Y MB per launch"
     except (OSError, ValueError, IndexError):
         pass
     return None
@@ -428,8 +428,6 @@ def main() -> int:
     # layers (fresh weights each launch, so no cache reuse) between two events on this stream.
     gemm = {}
     fused_on = not any(kv.replace(" ", "") == "gemm_fused=0" for kv in args.param)
-    tot_bytes = tot_ms = 0.0
-    n_launch = 0
     for kind, kname in enumerate(GEMM_KINDS):
         rows = 1 if kind >= 5 else sum(1 if f else T for f in flags)
         reps = 3 if kind <= 3 else 20
@@ -450,11 +448,23 @@ def main() -> int:
         fused_kind = kind in (0, 2) and rows <= 64 and fused_on
         gemm[kname]["kernel"] = ("k_qkv_rope" if kind == 0 else "k_gate_up_swiglu") if fused_kind else (
             "k_gemm_bf16<4,2,1>" if kind <= 4 else "k_gemm_bf16<1,2,1>")
-        if kind <= 4 and not fused_kind:
-            tot_bytes += nbytes
-            tot_ms += ms
-            n_launch += launches
+    # the roofline object covers the kernel of the layer stack that takes the most time in a step
+    by_kernel = {}
+    for kname in GEMM_KINDS[:5]:
+        g = by_kernel.setdefault(gemm[kname]["kernel"], {"kinds": [], "ms_per_step": 0.0, "bytes": 0.0, "launches": 0})
+        g["kinds"].append(kname)
+        g["ms_per_step"] += gemm[kname]["ms_per_step"]
+        g["bytes"] += gemm[kname]["GB"] * 1e9
+        g["launches"] += gemm[kname]["launches"]
+    for g in by_kernel.values():
+        g["GBps"] = round(g["bytes"] / g["ms_per_step"] / 1e6, 1)
+        g["frac"] = round(g["bytes"] / g["ms_per_step"] / 1e6 / HBM_PEAK_GBS, 4)
+        g["ms_per_step"] = round(g["ms_per_step"], 4)
+    dom = max(by_kernel, key=lambda k: by_kernel[k]["ms_per_step"])
+    tot_bytes, tot_ms, n_launch = by_kernel[dom]["bytes"], by_kernel[dom]["ms_per_step"], by_kernel[dom]["launches"]
     achieved = tot_bytes / tot_ms / 1e6
+    for g in by_kernel.values():
+        del g["bytes"]
     alg = algorithmic_bytes(cfg, T, L)
     if Bn > 1 or args.ar:               # weights once; KV rows and tree rows per sequence; heads only if some sequence runs them
         per = [algorithmic_bytes(cfg, 1 if f else T, l) for f, l in zip(flags, Ls)]
@@ -503,13 +513,14 @@ def main() -> int:
         "step_mfma_frac": round(t_mfma / step_s, 4),
         "step_bound": {"hbm_time_at_peak_ms": round(t_hbm * 1e3, 3), "mfma_time_at_peak_ms": round(t_mfma * 1e3, 3),
                        "binding": "hbm" if t_hbm >= t_mfma else "mfma", "rows": rows_step, "sum_prefix": int(sum(Ls))},
-        "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<4,2,1> (" + ", ".join(k for k, v in gemm.items() if v["kernel"] == "k_gemm_bf16<4,2,1>") + ")",
+        "roofline": {"bound": "hbm", "kernel": dom + " (" + ", ".join(by_kernel[dom]["kinds"]) + ")",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": (profiled_traffic_mb() if name == "7b" and L == 1024 and Bn == 1 and T == 64 and not args.ar else None),
+                     "traffic": (profiled_traffic_mb(dom) if name == "7b" and L == 1024 and Bn == 1 and T == 64 and not args.ar else None),
                      "traffic_unit": "MB per launch",
                      "traffic_source": "read from the committed summary profiles/verify_step_7b_t64_l1024.txt (rocprofv3 --pmc "
                                        "FETCH_SIZE + WRITE_SIZE of an earlier run of this command); not measured by this run",
+                     "by_kernel": by_kernel,
                      "mfma": mfma,
                      "algorithmic_MB_per_launch": round(tot_bytes / n_launch / 1e6, 1),
                      "avg_launch_us": round(tot_ms * 1e3 / n_launch, 2), "launches_per_step": n_launch,
