@@ -294,6 +294,8 @@ def main() -> int:
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling profiler byte counters)")
     args = ap.parse_args()
+    if args.ar_direct:
+        args.ar = True          # same step kind, rows and byte count; only the entry point differs (launches sized for one row)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path has no inter-GPU part); run with --gpus 1",
               file=sys.stderr)
@@ -427,7 +429,6 @@ def main() -> int:
     # dominant kernel: the weight-streaming GEMM.  Every kind is replayed back to back over all
     # layers (fresh weights each launch, so no cache reuse) between two events on this stream.
     gemm = {}
-    fused_on = not any(kv.replace(" ", "") == "gemm_fused=0" for kv in args.param)
     for kind, kname in enumerate(GEMM_KINDS):
         rows = 1 if kind >= 5 else sum(1 if f else T for f in flags)
         reps = 3 if kind <= 3 else 20
@@ -445,7 +446,7 @@ def main() -> int:
                        "GBps": round(nbytes / ms / 1e6, 1), "us_per_launch": round(ms * 1e3 / launches, 2)}
         # the dominant kernel is the split-K GEMM instance for tree rows (O, down, LM head; also QKV and gate/up
         # where the step does not run those as whole-K fused launches); head GEMMs run the 16-row instance
-        fused_kind = kind in (0, 2) and rows <= 64 and fused_on
+        fused_kind = kind in (0, 2) and B.cerberus_bench_gemm(eng.ctx, 100 + kind, rows) == 1.0
         gemm[kname]["kernel"] = ("k_qkv_rope" if kind == 0 else "k_gate_up_swiglu") if fused_kind else (
             "k_gemm_bf16<4,2,1>" if kind <= 4 else "k_gemm_bf16<1,2,1>")
     # the roofline object covers the kernel of the layer stack that takes the most time in a step
@@ -503,7 +504,7 @@ def main() -> int:
                                    "tokens_per_s = prompt tokens" if args.prefill else "")
                                 if Bn == 1 and not args.ar else
                                 f"{name}-shape bf16, batch {Bn}, KV prefixes {Ls}, step kinds (1 = auto-regressive) {flags}, "
-                                f"{T}-node tree"),
+                                f"{T}-node tree" + (", cerberus_ar_step called directly" if args.ar_direct else "")),
                    "graph": graph is not None},
         "latency_us": {"p10": round(float(np.percentile(lat, 10)), 1), "p50": round(float(np.percentile(lat, 50)), 1),
                        "p90": round(float(np.percentile(lat, 90)), 1)},

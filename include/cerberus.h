@@ -225,7 +225,8 @@ int cerberus_set_param(cerberus_ctx *ctx, const char *name, int32_t value);
  * 3 FFN down, 4 LM head, 5 head Resblocks (all stages), 6 head FC.  Where a step of `rows` rows runs the
  * QKV or gate/up projection as a whole-K fused launch, so does the hook (over the rows of the last
  * step's row map, which must have had that many; without the cache write).  Writes to *bytes (HOST, may
- * be NULL) the weight + activation bytes the launches read once each.                          */
+ * be NULL) the weight + activation bytes the launches read once each.  kind + 100 launches nothing
+ * and writes 1.0 if a step of `rows` rows runs that kind as a whole-K fused launch, else 0.0.  */
 int cerberus_bench_gemm(cerberus_ctx *ctx, int32_t kind, int32_t rows, void *stream, double *bytes);
 
 /* Text of the last error raised on this thread (never NULL).                                   */

@@ -865,6 +865,12 @@ int cerberus_accept_noalloc(cerberus_ctx* ctx, const int32_t* node_argmax, const
 int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* stream, double* bytes) {
   if (!ctx) return fail(CERBERUS_ERR_ARG, "null context");
   const Dims& D = ctx->D;
+  if (kind >= 100 && kind <= 106) {   // query: would a step of this many rows run the kind as a whole-K fused launch?
+    const bool f = ctx->use_fused && D.dtype == CERBERUS_BF16 && rows >= 1 && rows <= 64 && ctx->fused_grid > 0 && ctx->act_split == 1 &&
+                   ((kind == 100 && ctx->ns_qkv) || (kind == 102 && ctx->ns_gu));
+    if (bytes) *bytes = f ? 1.0 : 0.0;
+    return CERBERUS_OK;
+  }
   const bool head_kind = kind == 5 || kind == 6;
   if (kind < 0 || kind > 6) return fail(CERBERUS_ERR_ARG, "kind out of 0..6");
   if (rows < 1 || rows > (head_kind ? D.Bmax : D.Bmax * D.T)) return fail(CERBERUS_ERR_ARG, "rows out of range");
