@@ -72,6 +72,7 @@ struct cerberus_ctx {
   float* final_norm = nullptr;
   std::vector<float*> attn_norm, ffn_norm, res_b;
   std::vector<void*> pk_qkv, pk_o, pk_gu, pk_down, pk_res, pk_fc;
+  std::vector<void*> st_qkv, st_gu;      // stream-order copies of the QKV and gate/up weights for the whole-K kernels
   void* pk_lm = nullptr;
   size_t small_bytes = 0;  // everything before the packed weights
 
@@ -88,7 +89,7 @@ struct cerberus_ctx {
   GemmBatch p_lm{}, p_fc{};
 
   // whole-K fused GEMMs (bf16 mode, launches of up to 64 rows): which slabs every workgroup owns
-  int fused_grid = 0;                    // workgroups = compute units of the device (0: not set up)
+  int fused_grid = 0;                    // workgroups of a whole-K launch (0: not set up)
   int *slabs_qkv = nullptr, *slabs_gu = nullptr;   // device tables [kFusedMaxGrid][ns]
   int ns_qkv = 0, ns_gu = 0;             // positions per workgroup; 0 = that GEMM stays on the split-K path
   int use_fused = 1;
@@ -99,6 +100,8 @@ struct cerberus_ctx {
 namespace {
 
 constexpr int kFusedMaxGrid = 512, kFusedMaxNs = 6;
+constexpr int kFusedGrid = 256;          // one workgroup per compute unit of an MI355X; fixed, so that the workspace
+                                         // (which holds weight copies laid out for this grid) can be sized without a device
 
 // Scratch of cerberus_accept_noalloc (the acceptance entry point for callers that cannot pass or
 // allocate a workspace): the row map, the accepted path and the last-row list, for up to
@@ -176,6 +179,8 @@ void fill_dims(cerberus_ctx* c, const cerberus_config* cfg, const cerberus_tree*
   D.R64 = c->R64;
   c->n_chunks_max = ceil_div(cfg->kv_capacity, 128) + ceil_div(std::max(t->n_nodes, c->prompt_rows), 64);  // committed-row chunks + tree chunks
 }
+
+int fused_tables(const Dims& D, int grid, std::vector<int>& qkv, int& ns_qkv, std::vector<int>& gu, int& ns_gu);
 
 // Assigns every workspace pointer of the context; with base == nullptr it only measures.
 size_t layout(cerberus_ctx* c, unsigned char* base) {
@@ -257,6 +262,17 @@ size_t layout(cerberus_ctx* c, unsigned char* base) {
       c->pk_qkv[l] = pk(3 * d, d); c->pk_o[l] = pk(d, d); c->pk_gu[l] = pk(2 * D.F, d); c->pk_down[l] = pk(d, D.F);
     }
     c->pk_lm = pk(D.V, d);
+    {
+      // whole-K kernels: slab tables for the fixed grid, and a copy of the QKV and gate/up weights in their stream order
+      std::vector<int> tq, tg;
+      fused_tables(D, kFusedGrid, tq, c->ns_qkv, tg, c->ns_gu);
+      const int ksteps = kpad(cfg, d) / 32;
+      c->st_qkv.assign(D.n_layers, nullptr); c->st_gu.assign(D.n_layers, nullptr);
+      for (int l = 0; l < D.n_layers; ++l) {
+        if (c->ns_qkv) c->st_qkv[l] = b.take<uint4>(fused_stream_pieces(c->ns_qkv, kFusedGrid, ksteps));
+        if (c->ns_gu) c->st_gu[l] = b.take<uint4>(fused_stream_pieces(c->ns_gu, kFusedGrid, ksteps));
+      }
+    }
     c->pk_res.assign((size_t)D.Hc * D.R, nullptr);
     c->pk_fc.assign(D.Hc, nullptr);
     for (int i = 0; i < D.Hc; ++i) {
@@ -474,7 +490,7 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
 int run_fused_qkv(const cerberus_ctx* c, int l, void* kv_layer, hipStream_t s) {
   const Dims& D = c->D;
   FusedQkvArgs fa{};
-  fa.W = c->wqkv[l]; fa.At = c->xn; fa.slabs = c->slabs_qkv; fa.ksteps = kpad(c->cfg, D.d) / 32; fa.ssq = c->ssq;
+  fa.W = c->st_qkv[l]; fa.At = c->xn; fa.slabs = c->slabs_qkv; fa.ksteps = kpad(c->cfg, D.d) / 32; fa.ssq = c->ssq;
   fa.nb = add_gain_blocks(D.d); fa.rope_cs = c->rope_cs; fa.rm = c->rm; fa.q = (bf16_t*)c->q; fa.kv_layer = (bf16_t*)kv_layer;
   fa.ktree = (bf16_t*)c->ktree; fa.vtree = (bf16_t*)c->vtree; fa.lo_off = (size_t)c->R64 * D.d; fa.D = D;
   HIP_TRY(launch_qkv_rope(fa, c->ns_qkv, c->fused_grid, s));
@@ -484,7 +500,7 @@ int run_fused_qkv(const cerberus_ctx* c, int l, void* kv_layer, hipStream_t s) {
 int run_fused_gate_up(const cerberus_ctx* c, int l, hipStream_t s) {
   const Dims& D = c->D;
   FusedGateUpArgs ga{};
-  ga.W = c->wgu[l]; ga.At = c->xn; ga.slabs = c->slabs_gu; ga.ksteps = kpad(c->cfg, D.d) / 32; ga.ssq = c->ssq;
+  ga.W = c->st_gu[l]; ga.At = c->xn; ga.slabs = c->slabs_gu; ga.ksteps = kpad(c->cfg, D.d) / 32; ga.ssq = c->ssq;
   ga.nb = add_gain_blocks(D.d); ga.d = D.d; ga.eps = D.eps; ga.rm = c->rm; ga.act = (bf16_t*)c->act;
   ga.lo_off = (size_t)c->R64 * D.Fpad; ga.Fpad = D.Fpad;
   HIP_TRY(launch_gate_up_swiglu(ga, c->ns_gu, c->fused_grid, s));
@@ -764,13 +780,16 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
     }
   }
   if (D.dtype == CERBERUS_BF16) {
-    hipDeviceProp_t prop;
-    HIP_INIT(hipGetDeviceProperties(&prop, c->device));
-    c->fused_grid = std::min(prop.multiProcessorCount, (int)kFusedMaxGrid);
+    c->fused_grid = kFusedGrid;
     std::vector<int> tq, tg;
-    fused_tables(D, c->fused_grid, tq, c->ns_qkv, tg, c->ns_gu);
+    fused_tables(D, c->fused_grid, tq, c->ns_qkv, tg, c->ns_gu);     // the same tables the workspace was laid out for
     if (c->ns_qkv) HIP_INIT(hipMemcpy(c->slabs_qkv, tq.data(), tq.size() * sizeof(int), hipMemcpyHostToDevice));
     if (c->ns_gu) HIP_INIT(hipMemcpy(c->slabs_gu, tg.data(), tg.size() * sizeof(int), hipMemcpyHostToDevice));
+    const int ksteps = kpad(*cfg, d) / 32;
+    for (int l = 0; l < D.n_layers; ++l) {
+      if (c->ns_qkv) HIP_INIT(launch_pack_stream(c->pk_qkv[l], c->st_qkv[l], c->slabs_qkv, c->ns_qkv, c->fused_grid, ksteps, s0));
+      if (c->ns_gu) HIP_INIT(launch_pack_stream(c->pk_gu[l], c->st_gu[l], c->slabs_gu, c->ns_gu, c->fused_grid, ksteps, s0));
+    }
   }
   HIP_INIT(hipDeviceSynchronize());
 #undef HIP_INIT

@@ -57,7 +57,7 @@ hipError_t launch_rope_kv(const Dims& D, const RowMap& rm, const float* part, in
 // of row mt*16 + lane%16 at columns ks*32 + (lane/16)*8.., plane 0 = hi, 1 = lo (written by launch_add_gain
 // with a_tiled).  slabs: [grid][ns] 16-column slabs of every workgroup, -1 = none; positions (2p, 2p+1) form a pair.
 struct FusedQkvArgs {
-  const void* W;            // packed [3d][K]
+  const void* W;            // [3d][K] in the stream order of this kernel's grid and slab table (launch_pack_stream)
   const void* At;
   const int* slabs;         // pairs: slabs i and i + dh/32 of a q or k head; or one or two v slabs
   int ksteps;               // padded K / 32
@@ -73,7 +73,7 @@ struct FusedQkvArgs {
   Dims D;
 };
 struct FusedGateUpArgs {
-  const void* W;            // packed [2F][K], gate rows first
+  const void* W;            // [2F][K] (gate rows first) in the stream order of this kernel's grid and slab table
   const void* At;
   const int* slabs;         // pairs: (gate slab s, up slab F/16 + s): the same 16 FFN columns
   int ksteps;
@@ -87,6 +87,8 @@ struct FusedGateUpArgs {
 };
 hipError_t launch_qkv_rope(const FusedQkvArgs& a, int ns, int grid, hipStream_t s);
 hipError_t launch_gate_up_swiglu(const FusedGateUpArgs& a, int ns, int grid, hipStream_t s);
+size_t fused_stream_pieces(int ns, int grid, int ksteps);   // 16-byte pieces of a stream-order weight copy
+hipError_t launch_pack_stream(const void* packed, void* dst, const int* table, int ns, int grid, int ksteps, hipStream_t s);
 hipError_t launch_swiglu(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, void* act,
                          const float* ssq, int rows_max, hipStream_t s);
 hipError_t launch_row_argmax(const Dims& D, const RowMap& rm, const float* part, int S, size_t pstride, int* g,
