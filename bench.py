@@ -448,7 +448,8 @@ def main() -> int:
         # where the step does not run those as whole-K fused launches); head GEMMs run the 16-row instance
         fused_kind = kind in (0, 2) and B.cerberus_bench_gemm(eng.ctx, 100 + kind, rows) == 1.0
         gemm[kname]["kernel"] = ("k_qkv_rope" if kind == 0 else "k_gate_up_swiglu") if fused_kind else (
-            "k_gemm_bf16<4,2,1>" if kind <= 4 else "k_gemm_bf16<1,2,1>")
+            "k_gemm_bf16<1,2,1,true>" if kind > 4 else "k_gemm_bf16_rows<1>" if rows > 256 and kind in (3, 4)
+            else "k_gemm_bf16<4,2,1,%s>" % ("true" if rows <= 64 else "false"))
     # the roofline object covers the kernel of the layer stack that takes the most time in a step
     by_kernel = {}
     for kname in GEMM_KINDS[:5]:

@@ -9,11 +9,21 @@ typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
 // round-to-nearest-even (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return __builtin_bit_cast(bf16_t, static_cast<__bf16>(f)); }
+
+// 16 bytes of a weight matrix that a launch streams through: loaded with the streaming hint, so that the lines
+// leave the caches first and the activation fragments every workgroup re-reads stay.
+__device__ __forceinline__ uint4 ld_weight_once(const uint4* p) {
+  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(t[0], t[1], t[2], t[3]);
+}
+
+template <bool ONCE> __device__ __forceinline__ uint4 ld_w(const uint4* p) { return ONCE ? ld_weight_once(p) : *p; }
 
 template <typename T> __device__ __forceinline__ float ld_f(const T* p);
 template <> __device__ __forceinline__ float ld_f<float>(const float* p) { return *p; }

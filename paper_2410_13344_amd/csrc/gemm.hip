@@ -63,7 +63,9 @@ __device__ __forceinline__ bool gemm_skip(const GemmBatch& g) {
   return all;
 }
 
-template <int MT, int NSUB, int SPLIT>
+// ONCE: the launch has a single row block, every weight byte is read by exactly one workgroup: streaming loads.
+// (With several row blocks the repeats are meant to hit in L2, and the streaming hint costs 10-20 %.)
+template <int MT, int NSUB, int SPLIT, bool ONCE>
 __device__ __forceinline__ void gemm_bf16_body(const GemmBatch& g) {
   if (gemm_skip(g)) return;
   const int rows = g.n_rows ? *g.n_rows : g.rows_static;
@@ -166,7 +168,7 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmBatch& g) {
 #pragma unroll
   for (int i = 0; i < kRing; ++i)     // slot kRing - 1 is filled by the first k-step of the loop (its load below is not waited for)
 #pragma unroll
-    for (int j = 0; j < NSUB; ++j) ring[i][j] = wp[j][(size_t)min(ks0 + min(i, kRing - 2), ks1 - 1) * 64];
+    for (int j = 0; j < NSUB; ++j) ring[i][j] = ld_w<ONCE>(wp[j] + (size_t)min(ks0 + min(i, kRing - 2), ks1 - 1) * 64);
   CERB_A_ST(P, 0, 0)
   CERB_A_LD(P, min(1, nchunks - 1), 0)
   __syncthreads();
@@ -185,7 +187,7 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmBatch& g) {
       /* chunk get hoisted to its top, where they wait for every load in flight.)  The scheduling barrier keeps   */       \
       /* the load here instead of wherever the scheduler would sink it.                                           */       \
       _Pragma("unroll") for (int j = 0; j < NSUB; ++j)                                                                    \
-        ring[((PAR) * KSC + s + kRing - 1) % kRing][j] = wp[j][(size_t)min(kb + s + kRing - 1, ks1 - 1) * 64];            \
+        ring[((PAR) * KSC + s + kRing - 1) % kRing][j] = ld_w<ONCE>(wp[j] + (size_t)min(kb + s + kRing - 1, ks1 - 1) * 64);   \
       __builtin_amdgcn_sched_barrier(0);                                                                                  \
       const uint4* b = ring[((PAR) * KSC + s) % kRing];                                                                   \
       _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) if (FULL || mt < mt_n) {                                                  \
@@ -241,9 +243,9 @@ __device__ __forceinline__ void gemm_bf16_body(const GemmBatch& g) {
 }
 
 // Two workgroups per CU: the weight-streaming instances, whose time goes to loads in flight.
-template <int MT, int NSUB, int SPLIT>
+template <int MT, int NSUB, int SPLIT, bool ONCE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_gemm_bf16(const GemmBatch g) {
-  gemm_bf16_body<MT, NSUB, SPLIT>(g);
+  gemm_bf16_body<MT, NSUB, SPLIT, ONCE>(g);
 }
 
 // One workgroup per CU with the whole register file: 64 rows x 4 slabs per wave.  Launches of several
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 // once serves four slabs here instead of two.
 template <int SPLIT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_bf16_rows(const GemmBatch g) {
-  gemm_bf16_body<4, 4, SPLIT>(g);
+  gemm_bf16_body<4, 4, SPLIT, false>(g);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -286,12 +288,15 @@ static void launch_bf16(const GemmBatch& g, dim3 grid, hipStream_t s) {
   if (MT == 4 && g.nsub == 4) {
     if (g.split) hipLaunchKernelGGL((k_gemm_bf16_rows<1>), grid, dim3(256), 0, s, g);
     else hipLaunchKernelGGL((k_gemm_bf16_rows<0>), grid, dim3(256), 0, s, g);
-  } else if (g.nsub == 4) {
-    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 1>), grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 0>), grid, dim3(256), 0, s, g);
+  } else if (g.nsub == 4) {        // (MT < 4 here: one row block)
+    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 1, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<MT, 4, 0, true>), grid, dim3(256), 0, s, g);
+  } else if (MT < 4 || g.row_blocks == 1) {
+    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 2, 1, true>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<MT, 2, 0, true>), grid, dim3(256), 0, s, g);
   } else {
-    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<MT, 2, 1>), grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((k_gemm_bf16<MT, 2, 0>), grid, dim3(256), 0, s, g);
+    if (g.split) hipLaunchKernelGGL((k_gemm_bf16<4, 2, 1, false>), grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<4, 2, 0, false>), grid, dim3(256), 0, s, g);
   }
 }
 

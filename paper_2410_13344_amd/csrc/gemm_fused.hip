@@ -51,7 +51,7 @@ __device__ __forceinline__ void whole_k_accumulate(const uint4* __restrict__ W, 
   for (int i = 0; i < DB - 1; ++i)
 #pragma unroll
     for (int j = 0; j < NS; ++j)
-      if (slab[j] >= 0) rb[i][j] = wp[j][(size_t)min(i, ks1 - ks0 - 1) * wstep];
+      if (slab[j] >= 0) rb[i][j] = ld_weight_once(wp[j] + (size_t)min(i, ks1 - ks0 - 1) * wstep);
 #pragma unroll
   for (int i = 0; i < DA - 1; ++i)
 #pragma unroll
@@ -64,7 +64,7 @@ __device__ __forceinline__ void whole_k_accumulate(const uint4* __restrict__ W, 
       const int ks = base + i;
 #pragma unroll
       for (int j = 0; j < NS; ++j)
-        if (slab[j] >= 0) rb[(i + DB - 1) % DB][j] = wp[j][(size_t)min(ks + DB - 1 - ks0, ks1 - ks0 - 1) * wstep];
+        if (slab[j] >= 0) rb[(i + DB - 1) % DB][j] = ld_weight_once(wp[j] + (size_t)min(ks + DB - 1 - ks0, ks1 - ks0 - 1) * wstep);
 #pragma unroll
       for (int f = 0; f < 8; ++f)
         if (FULL || (f & 3) < mt_n) ra[(i + DA - 1) % DA][f] = ap[(size_t)(min(ks + DA - 1, ks1 - 1) * 8 + f) * 64];
