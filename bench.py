@@ -148,10 +148,10 @@ def cpu_baseline_schedule(cfg, W_dev, parent, rank, kv_t, L, root, cand, n_tree,
             "measured_s": round(sum(tt) + sum(ta), 3)}
 
 
-def profiled_traffic_mb(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of the default workload
-    (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy), or None when the summary has no line for it."""
-    path = os.path.join(ROOT, "profiles", "verify_step_7b_t64_l1024.txt")
+def profiled_traffic_mb(kernel, summary):
+    """HBM bytes per launch of `kernel` from a committed rocprofv3 --pmc summary under profiles/ (FETCH_SIZE +
+    WRITE_SIZE, scaled by the calibration copy), or None when the summary has no line for it."""
+    path = os.path.join(ROOT, "profiles", summary)
     try:
         for line in open(path):
             if line.startswith(f"traffic {kernel}:"):
@@ -467,6 +467,13 @@ def main() -> int:
     achieved = tot_bytes / tot_ms / 1e6
     for g in by_kernel.values():
         del g["bytes"]
+    # the two workloads whose committed profile carries the counter passes
+    pmc_summary = None
+    if name == "7b" and T == 64 and not args.ar:
+        if Bn == 1 and L == 1024:        # (also the decode, prefill and independent-heads runs: same kernel, same rows)
+            pmc_summary = "verify_step_7b_t64_l1024.txt"
+        elif Bn == 8 and args.mixed and args.prefix is None and not args.decode and not args.prefill and not args.medusa_heads:
+            pmc_summary = "verify_step_7b_batch8_mixed.txt"
     alg = algorithmic_bytes(cfg, T, L)
     if Bn > 1 or args.ar:               # weights once; KV rows and tree rows per sequence; heads only if some sequence runs them
         per = [algorithmic_bytes(cfg, 1 if f else T, l) for f, l in zip(flags, Ls)]
@@ -518,10 +525,11 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dom + " (" + ", ".join(by_kernel[dom]["kinds"]) + ")",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": (profiled_traffic_mb(dom) if name == "7b" and L == 1024 and Bn == 1 and T == 64 and not args.ar else None),
+                     "traffic": profiled_traffic_mb(dom, pmc_summary) if pmc_summary else None,
                      "traffic_unit": "MB per launch",
-                     "traffic_source": "read from the committed summary profiles/verify_step_7b_t64_l1024.txt (rocprofv3 --pmc "
-                                       "FETCH_SIZE + WRITE_SIZE of an earlier run of this command); not measured by this run",
+                     "traffic_source": (f"read from the committed summary profiles/{pmc_summary} (rocprofv3 --pmc FETCH_SIZE + "
+                                        "WRITE_SIZE of an earlier run of this command); not measured by this run") if pmc_summary
+                                       else "no counter summary is committed for this workload",
                      "by_kernel": by_kernel,
                      "mfma": mfma,
                      "algorithmic_MB_per_launch": round(tot_bytes / n_launch / 1e6, 1),
