@@ -45,6 +45,22 @@ template <> __device__ __forceinline__ void st_a<bf16_t>(bf16_t* p, size_t lo_of
   p[lo_off] = f32_to_bf16(v - bf16_to_f32(hi));
 }
 
+// four consecutive values of a GEMM input row; p (and the lo plane) aligned to the four elements
+template <typename T> __device__ __forceinline__ void st_a4(T* p, size_t lo_off, const float (&v)[4]);
+template <> __device__ __forceinline__ void st_a4<float>(float* p, size_t, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void st_a4<bf16_t>(bf16_t* p, size_t lo_off, const float (&v)[4]) {
+  union { bf16_t h[4]; uint2 u; } hi, lo;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    hi.h[e] = f32_to_bf16(v[e]);
+    lo.h[e] = f32_to_bf16(v[e] - bf16_to_f32(hi.h[e]));
+  }
+  *reinterpret_cast<uint2*>(p) = hi.u;
+  *reinterpret_cast<uint2*>(p + lo_off) = lo.u;
+}
+
 // ---------------------------------------------------------------------------------------------
 // per-step row map: packed rows of all sequences (sequence b owns rows seq_row0[b] .. +seq_T[b])
 // ---------------------------------------------------------------------------------------------
