@@ -207,6 +207,9 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  *   "gemm_nsub_rows"  (0, 2 or 4, default 0)   the same for launches of more than 64 rows (several row blocks);
  *                                              4 runs one workgroup per CU with the whole register file; 0 picks
  *                                              4 for the down projection and the LM head past 256 rows, else 2
+ *   "gemm_team"       (0 or 1, default 1)      1: bf16 launches of more than 128 rows run the gate/up projection on
+ *                                              the kernel that deals (column block, k) ranges to teams of one
+ *                                              workgroup per 128-row block; 0: on the same kernel as the others
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)
  *   "attn_chunk"      (128 or 256, default 128) committed cache rows per round of an attention workgroup

@@ -9,7 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcerberus.so")
-SOURCES = ["gemm.hip", "gemm_fused.hip", "attention.hip", "step_kernels.hip", "cerberus_api.hip"]
+SOURCES = ["gemm.hip", "gemm_fused.hip", "gemm_team.hip", "attention.hip", "step_kernels.hip", "cerberus_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

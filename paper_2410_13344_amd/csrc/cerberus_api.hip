@@ -84,7 +84,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0, prompt_rows = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, gemm_team = 1, gemm_team_teams = 0, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
 
@@ -421,7 +421,7 @@ void build_plans(cerberus_ctx* c) {
   for (int l = 0; l < L; ++l) {
     { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, 64, false); }
     { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wo[l], &N, &K, 64, false); }
-    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, 64, false); }
+    { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, 64, false); c->p_gu[l].team_rows = 1; }
     { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, 64, false); c->p_down[l].wide_rows = 1; }
   }
   { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, 64, false); c->p_lm.wide_rows = 1; }
@@ -461,6 +461,26 @@ int check_state(const cerberus_ctx* c, const cerberus_state* st, int batch) {
 int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, int rows_static, int rows_max,
              const int* skip_flags, int n_skip, hipStream_t s, GemmProb* launched = nullptr) {
   GemmBatch g = plan;
+  // Above 128 rows the problems the planner marked (wide weights: the gate/up projection) run on the team kernel,
+  // which streams the weights once per team of row blocks; its partial planes are the split of the launch.
+  TeamPlan tp;
+  if (launched && plan.team_rows && c->gemm_team && c->cfg.dtype == CERBERUS_BF16 && g.split && g.n_prob == 1 && !skip_flags &&
+      c->fused_grid >= 8 && g.p[0].lda >= g.p[0].K &&   // (the kernel reads whole padded rows)
+      plan_team_gemm(rows_max, g.p[0].N, g.p[0].K, c->fused_grid, c->max_split, &tp, c->gemm_team_teams) &&
+      (size_t)tp.planes * align_up((size_t)rows_max, 64) * g.p[0].N <= c->part_floats) {
+    GemmProb& P = g.p[0];
+    P.out_rows = (int)align_up((size_t)rows_max, 64);
+    P.S = tp.planes; P.kps = 0; P.rem = 0;
+    P.out = c->part;
+    TeamGemmArgs ta{};
+    ta.W = reinterpret_cast<const uint4*>(P.W); ta.A = reinterpret_cast<const bf16_t*>(P.A); ta.lo_off = P.lo_off; ta.lda = P.lda;
+    ta.out = P.out; ta.out_rows = P.out_rows; ta.N = P.N; ta.ksteps = P.K / 32;
+    ta.n_rows = n_rows; ta.rows_static = std::min(rows_static, rows_max); ta.rows_per = tp.rows_per;
+    ta.RB = tp.RB; ta.T = tp.T; ta.P = tp.planes;
+    *launched = P;
+    HIP_TRY(launch_team_gemm(ta, tp, s));
+    return CERBERUS_OK;
+  }
   // plans are made for 17..64 rows; other row counts run other kernel instances or several row
   // blocks and get their own split (only where the caller takes the launched description back)
   if (launched && (rows_max > 64 || rows_max <= 16)) {
@@ -781,6 +801,7 @@ int cerberus_init(cerberus_ctx** out, const cerberus_config* cfg, const cerberus
   }
   if (D.dtype == CERBERUS_BF16) {
     c->fused_grid = kFusedGrid;
+    HIP_INIT(init_team_gemm());
     std::vector<int> tq, tg;
     fused_tables(D, c->fused_grid, tq, c->ns_qkv, tg, c->ns_gu);     // the same tables the workspace was laid out for
     if (c->ns_qkv) HIP_INIT(hipMemcpy(c->slabs_qkv, tq.data(), tq.size() * sizeof(int), hipMemcpyHostToDevice));
@@ -887,7 +908,10 @@ int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* str
   if (kind >= 100 && kind <= 106) {   // query: would a step of this many rows run the kind as a whole-K fused launch?
     const bool f = ctx->use_fused && D.dtype == CERBERUS_BF16 && rows >= 1 && rows <= 64 && ctx->fused_grid > 0 && ctx->act_split == 1 &&
                    ((kind == 100 && ctx->ns_qkv) || (kind == 102 && ctx->ns_gu));
-    if (bytes) *bytes = f ? 1.0 : 0.0;
+    TeamPlan tp;
+    const bool team = kind == 102 && ctx->gemm_team && D.dtype == CERBERUS_BF16 && ctx->act_split == 1 && ctx->fused_grid >= 8 &&
+                      plan_team_gemm(rows, 2 * D.F, kpad(ctx->cfg, D.d), ctx->fused_grid, ctx->max_split, &tp, ctx->gemm_team_teams);
+    if (bytes) *bytes = f ? 1.0 : team ? 2.0 + tp.NT : 0.0;
     return CERBERUS_OK;
   }
   const bool head_kind = kind == 5 || kind == 6;
@@ -959,6 +983,12 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
   } else if (n == "attn_target_wgs") {
     if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "attn_target_wgs out of 1..65536");
     ctx->attn_target_wgs = value;
+  } else if (n == "gemm_team") {
+    if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "gemm_team must be 0 or 1");
+    ctx->gemm_team = value;
+  } else if (n == "gemm_team_teams") {
+    if (value < 0 || value > 256) return fail(CERBERUS_ERR_ARG, "gemm_team_teams out of 0..256");
+    ctx->gemm_team_teams = value;
   } else if (n == "gemm_nsub_rows") {
     if (value != 0 && value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub_rows must be 0, 2 or 4");
     ctx->gemm_nsub_rows = value;

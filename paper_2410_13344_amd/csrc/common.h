@@ -127,7 +127,28 @@ struct GemmBatch {
   int row_blocks;                // bf16: blocks of 64 rows in the launch (set by the launcher)
   int fixed_s1;                  // host side: the planner keeps split-K off (the consumer reads out[0] as the result)
   int wide_rows;                 // host side: launches of more than 256 rows take the 4-slab instance (down projection, LM head)
+  int team_rows;                 // host side: launches of more than 128 rows go to the team kernel (gate/up projection)
 };
+
+// GEMM of one problem over more than 128 rows by teams of workgroups (gemm_team.hip)
+struct TeamGemmArgs {
+  const uint4* W;        // pre-tiled weights: piece (slab, k-step) at (slab * ksteps + ks) * 64 sixteen-byte pieces
+  const bf16_t* A;       // [rows][lda] hi plane, the lo plane lo_off elements later
+  size_t lo_off;
+  int lda;
+  float* out;            // [P][out_rows][N]
+  int out_rows, N, ksteps;
+  const int* n_rows;     // device row count, or nullptr -> rows_static
+  int rows_static;
+  int rows_per;          // rows of a row block (a multiple of 16, at most 128)
+  int RB, T, P;          // row blocks, teams, partial planes
+};
+struct TeamPlan {
+  int RB, rows_per, NT, T, planes, grid;
+};
+bool plan_team_gemm(int rows_max, int N, int Kpad, int cus, int max_planes, TeamPlan* tp, int teams = 0);   // teams: 0 = one workgroup per CU
+hipError_t init_team_gemm();
+hipError_t launch_team_gemm(const TeamGemmArgs& a, const TeamPlan& tp, hipStream_t s);
 
 // launchers (defined next to their kernels)
 hipError_t launch_gemm(const GemmBatch& g, int dtype, int rows_max, hipStream_t s);
