@@ -84,7 +84,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0, prompt_rows = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, gemm_team = 1, gemm_team_teams = 0, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, gemm_team = 1, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
 
@@ -466,7 +466,7 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
   TeamPlan tp;
   if (launched && plan.team_rows && c->gemm_team && c->cfg.dtype == CERBERUS_BF16 && g.split && g.n_prob == 1 && !skip_flags &&
       c->fused_grid >= 8 && g.p[0].lda >= g.p[0].K &&   // (the kernel reads whole padded rows)
-      plan_team_gemm(rows_max, g.p[0].N, g.p[0].K, c->fused_grid, c->max_split, &tp, c->gemm_team_teams) &&
+      plan_team_gemm(rows_max, g.p[0].N, g.p[0].K, c->fused_grid, c->max_split, &tp) &&
       (size_t)tp.planes * align_up((size_t)rows_max, 64) * g.p[0].N <= c->part_floats) {
     GemmProb& P = g.p[0];
     P.out_rows = (int)align_up((size_t)rows_max, 64);
@@ -475,8 +475,7 @@ int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, in
     TeamGemmArgs ta{};
     ta.W = reinterpret_cast<const uint4*>(P.W); ta.A = reinterpret_cast<const bf16_t*>(P.A); ta.lo_off = P.lo_off; ta.lda = P.lda;
     ta.out = P.out; ta.out_rows = P.out_rows; ta.N = P.N; ta.ksteps = P.K / 32;
-    ta.n_rows = n_rows; ta.rows_static = std::min(rows_static, rows_max); ta.rows_per = tp.rows_per;
-    ta.RB = tp.RB; ta.T = tp.T; ta.P = tp.planes;
+    ta.n_rows = n_rows; ta.rows_static = rows_static; ta.rows_cap = rows_max; ta.rb_min = tp.rb_min; ta.P = tp.planes;
     *launched = P;
     HIP_TRY(launch_team_gemm(ta, tp, s));
     return CERBERUS_OK;
@@ -910,7 +909,7 @@ int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* str
                    ((kind == 100 && ctx->ns_qkv) || (kind == 102 && ctx->ns_gu));
     TeamPlan tp;
     const bool team = kind == 102 && ctx->gemm_team && D.dtype == CERBERUS_BF16 && ctx->act_split == 1 && ctx->fused_grid >= 8 &&
-                      plan_team_gemm(rows, 2 * D.F, kpad(ctx->cfg, D.d), ctx->fused_grid, ctx->max_split, &tp, ctx->gemm_team_teams);
+                      plan_team_gemm(rows, 2 * D.F, kpad(ctx->cfg, D.d), ctx->fused_grid, ctx->max_split, &tp);
     if (bytes) *bytes = f ? 1.0 : team ? 2.0 + tp.NT : 0.0;
     return CERBERUS_OK;
   }
@@ -986,9 +985,6 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
   } else if (n == "gemm_team") {
     if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "gemm_team must be 0 or 1");
     ctx->gemm_team = value;
-  } else if (n == "gemm_team_teams") {
-    if (value < 0 || value > 256) return fail(CERBERUS_ERR_ARG, "gemm_team_teams out of 0..256");
-    ctx->gemm_team_teams = value;
   } else if (n == "gemm_nsub_rows") {
     if (value != 0 && value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub_rows must be 0, 2 or 4");
     ctx->gemm_nsub_rows = value;

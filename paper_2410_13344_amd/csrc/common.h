@@ -140,13 +140,16 @@ struct TeamGemmArgs {
   int out_rows, N, ksteps;
   const int* n_rows;     // device row count, or nullptr -> rows_static
   int rows_static;
-  int rows_per;          // rows of a row block (a multiple of 16, at most 128)
-  int RB, T, P;          // row blocks, teams, partial planes
+  int rows_cap;          // upper bound of the row count the plan was made for
+  int rb_min;            // least number of row blocks (>= 2)
+  int P;                 // partial planes the consumer sums (an upper bound of what any row count needs)
 };
 struct TeamPlan {
-  int RB, rows_per, NT, T, planes, grid;
+  int NT, planes, grid;    // row tiles per workgroup, partial planes, workgroups
+  int rb_min;              // least number of row blocks the device may form
+  int RB, rows_per, T;     // row blocks, rows per block and teams if the launch has as many rows as the plan allows
 };
-bool plan_team_gemm(int rows_max, int N, int Kpad, int cus, int max_planes, TeamPlan* tp, int teams = 0);   // teams: 0 = one workgroup per CU
+bool plan_team_gemm(int rows_max, int N, int Kpad, int cus, int max_planes, TeamPlan* tp);
 hipError_t init_team_gemm();
 hipError_t launch_team_gemm(const TeamGemmArgs& a, const TeamPlan& tp, hipStream_t s);
 

@@ -58,26 +58,33 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   constexpr int N_W0 = 2 * NQ + 12;        // ... the weights of k-step 2n, after the issues before its products
   constexpr int N_W1 = NQ + 12;            // ... the weights of k-step 2n + 1
   extern __shared__ __attribute__((aligned(16))) u32x4_t team_lds[];
-  const int rows = a.n_rows ? *a.n_rows : a.rows_static;
+  const int rows = min(a.n_rows ? *a.n_rows : a.rows_static, a.rows_cap);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  // consecutive workgroup ids go to the 8 XCDs in turn: logical ids put a team's workgroups on one XCD
-  const int G = gridDim.x;                 // a multiple of 8
-  const int L = ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);
-  const int team = L / a.RB, rb = L - team * a.RB;
-  if (team >= a.T) return;
+  // The row count is known on the device only (the gate decides how many rows a sequence brings), so the row
+  // blocks and teams are formed here, by the same rule the host used for its bound (team_shape): as few row
+  // blocks as the NT row tiles of a workgroup allow, at least rb_min; the teams share the grid's workgroups.
+  const int RB = max(a.rb_min, (rows + NT * 16 - 1) / (NT * 16));
+  const int rows_per = ((rows + RB - 1) / RB + 15) / 16 * 16;
   const int nst = a.ksteps / kKC;
   const int nslab = a.N >> 4;
   const int CB = (nslab + kSPT - 1) / kSPT;
   const long long V = (long long)CB * nst;
-  const int v0 = (int)(V * team / a.T), v1 = (int)(V * (team + 1) / a.T);
+  const int T = (int)min((long long)((int)gridDim.x / RB), V);
+  // consecutive workgroup ids go to the 8 XCDs in turn: logical ids put a team's workgroups on one XCD
+  const int G = gridDim.x;                 // a multiple of 8
+  const int L = ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);
+  const int team = L / RB, rb = L - team * RB;
+  if (team >= T) return;
+  const int v0 = (int)(V * team / T), v1 = (int)(V * (team + 1) / T);
   const int len = v1 - v0;
   if (len <= 0) return;
-  const int m0 = rb * a.rows_per, m1 = min(rows, m0 + a.rows_per);
+  const int m0 = rb * rows_per, m1 = min(rows, m0 + rows_per);
   if (m0 >= m1) return;                    // (uniform over the workgroup: nobody is left at a barrier)
+  const int nt_live = (m1 - m0 + 15) >> 4; // row tiles of this workgroup that hold rows
 
   int cb = v0 / nst, st = v0 - cb * nst;   // the unit being multiplied
   // rank of this team among the teams of its first column block; any later block starts inside this team's range
-  int plane = team - ((int)((((long long)cb * nst + 1) * a.T + V - 1) / V) - 1);
+  int plane = team - ((int)((((long long)cb * nst + 1) * T + V - 1) / V) - 1);
 
   // ---- activations: fragment f = q * 8 + wave of a stage: row tile f >> 2, plane (f >> 1) & 1, k-step f & 1
   const unsigned lds_base = (unsigned)(unsigned long)((__attribute__((address_space(3))) const unsigned char*)team_lds);
@@ -139,9 +146,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     _Pragma("unroll") for (int i = 0; i < NT; ++i) {                                                            \
       u32x4_t nh = ah, nl = al;                                                                                 \
       if (i + 1 < NT) { nh = (sA)[((i + 1) * 2) * 64]; nl = (sA)[((i + 1) * 2 + 1) * 64]; }                     \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                           \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ah), __builtin_bit_cast(bf16x8_t, Wr[slot][j]), acc[i][j], 0, 0, 0); \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, al), __builtin_bit_cast(bf16x8_t, Wr[slot][j]), acc[i][j], 0, 0, 0); \
+      if (i < nt_live) {                                                                                        \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                         \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ah), __builtin_bit_cast(bf16x8_t, Wr[slot][j]), acc[i][j], 0, 0, 0); \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, al), __builtin_bit_cast(bf16x8_t, Wr[slot][j]), acc[i][j], 0, 0, 0); \
+        }                                                                                                       \
       }                                                                                                         \
       __builtin_amdgcn_sched_barrier(0);                                                                        \
       ah = nh; al = nl;                                                                                         \
@@ -228,25 +237,41 @@ hipError_t launch_nt(const TeamGemmArgs& a, int grid, hipStream_t s) {
 
 }  // namespace
 
-// Row blocks, teams and partial planes for a launch of up to rows_max rows on `cus` compute units; false where the
-// kernel does not apply (few rows, a shape it cannot tile, more planes than max_planes).
-bool plan_team_gemm(int rows_max, int N, int Kpad, int cus, int max_planes, TeamPlan* tp, int teams) {
-  if (rows_max <= 128 || N % 16 != 0 || Kpad % (32 * kKC) != 0 || cus < 8) return false;
-  const int RB = (rows_max + 127) / 128;
-  const int rows_per = ((rows_max + RB - 1) / RB + 15) / 16 * 16;
-  const int NT = rows_per / 16;
-  if (NT < 5 || NT > 8) return false;                 // (NT < 5 cannot happen above 128 rows)
+// The shape a launch takes for `rows` rows with NT row tiles per workgroup on `cus` workgroups (the kernel forms the
+// same on the device): row blocks, rows per block, teams, partial planes.
+static void team_shape(int rows, int NT, int rb_min, int N, int Kpad, int cus, int* RB, int* rows_per, int* T, int* planes) {
+  *RB = std::max(rb_min, (rows + NT * 16 - 1) / (NT * 16));
+  *rows_per = ((rows + *RB - 1) / *RB + 15) / 16 * 16;
   const int nst = Kpad / 32 / kKC, CB = (N / 16 + kSPT - 1) / kSPT;
   const long long V = (long long)CB * nst;
-  int T = teams > 0 ? std::min(teams, cus / RB) : cus / RB;
-  if (T < 1) return false;
-  if (T > V) T = (int)V;
-  int planes = 1;
+  *T = (int)std::min<long long>(cus / *RB, V);
+  *planes = 1;
+  if (*T < 1) return;
   for (int c = 0; c < CB; ++c)
-    planes = std::max(planes, team_of((long long)c * nst + nst - 1, T, V) - team_of((long long)c * nst, T, V) + 1);
+    *planes = std::max(*planes, team_of((long long)c * nst + nst - 1, *T, V) - team_of((long long)c * nst, *T, V) + 1);
+}
+
+// Plan for a launch of up to rows_max rows on `cus` compute units (a multiple of 8): the row tiles per workgroup and
+// the number of partial planes a consumer has to sum whatever the row count turns out to be; false where the kernel
+// does not apply (few rows, a shape it cannot tile, more planes than max_planes).
+bool plan_team_gemm(int rows_max, int N, int Kpad, int cus, int max_planes, TeamPlan* tp) {
+  if (rows_max <= 128 || N % 16 != 0 || Kpad % (32 * kKC) != 0 || cus < 8 || cus % 8 != 0) return false;
+  const int RBmax = (rows_max + 127) / 128;
+  const int NT = (((rows_max + RBmax - 1) / RBmax) + 15) / 16;
+  if (NT < 5 || NT > 8 || cus / RBmax < 1) return false;      // (NT < 5 cannot happen above 128 rows)
+  // the planes depend on the teams only, and the teams on the row blocks: every count the device may choose
+  // fewer row blocks mean more teams and more planes: small row counts keep nearly as many row blocks as the bound
+  const int rb_min = std::max(2, RBmax - 1);
+  int planes = 1;
+  for (int RB = rb_min; RB <= std::max(rb_min, (rows_max + NT * 16 - 1) / (NT * 16)); ++RB) {
+    int rb, rp, T, pl;
+    team_shape(RB * NT * 16, NT, rb_min, N, Kpad, cus, &rb, &rp, &T, &pl);
+    if (T < 1) return false;
+    planes = std::max(planes, pl);
+  }
   if (planes > max_planes) return false;
-  tp->RB = RB; tp->rows_per = rows_per; tp->NT = NT; tp->T = T; tp->planes = planes;
-  tp->grid = (T * RB + 7) / 8 * 8;
+  tp->NT = NT; tp->planes = planes; tp->grid = cus; tp->rb_min = rb_min;
+  team_shape(rows_max, NT, rb_min, N, Kpad, cus, &tp->RB, &tp->rows_per, &tp->T, &planes);   // (the shape at the bound, for reference)
   return true;
 }
 
