@@ -446,8 +446,8 @@ def main() -> int:
                        "GBps": round(nbytes / ms / 1e6, 1), "us_per_launch": round(ms * 1e3 / launches, 2)}
         # the dominant kernel is the split-K GEMM instance for tree rows (O, down, LM head; also QKV and gate/up
         # where the step does not run those as whole-K fused launches); head GEMMs run the 16-row instance
-        how = B.cerberus_bench_gemm(eng.ctx, 100 + kind, rows) if kind in (0, 2) else 0.0   # 1: whole-K fused, 2 + NT: team kernel
-        fused_kind = how == 1.0
+        how = B.cerberus_bench_gemm(eng.ctx, 100 + kind, rows) if kind in (0, 2, 4) else 0.0   # 1: whole-K fused, 2 + NT: team kernel
+        fused_kind = kind in (0, 2) and how == 1.0
         gemm[kname]["kernel"] = ("k_qkv_rope" if kind == 0 else "k_gate_up_swiglu") if fused_kind else "k_gemm_team<%d>" % int(how - 2) if how >= 2.0 else (
             "k_gemm_bf16<1,2,1,true>" if kind > 4 else "k_gemm_bf16_rows<1>" if rows > 256 and kind in (3, 4)
             else "k_gemm_bf16<4,2,1,%s>" % ("true" if rows <= 64 else "false"))

@@ -207,9 +207,11 @@ int cerberus_set_taps(cerberus_ctx *ctx, const cerberus_taps *taps);
  *   "gemm_nsub_rows"  (0, 2 or 4, default 0)   the same for launches of more than 64 rows (several row blocks);
  *                                              4 runs one workgroup per CU with the whole register file; 0 picks
  *                                              4 for the down projection and the LM head past 256 rows, else 2
- *   "gemm_team"       (0 or 1, default 1)      1: bf16 launches of more than 128 rows run the gate/up projection on
- *                                              the kernel that deals (column block, k) ranges to teams of one
- *                                              workgroup per 128-row block; 0: on the same kernel as the others
+ *   "gemm_team"       (0..3, default 3)        bf16 launches of more than 128 rows run, on the kernel that deals
+ *                                              (column block, k) ranges to teams of one workgroup per 128-row
+ *                                              block: 1 the gate/up projection, 2 also QKV and 3 also the LM head
+ *                                              (these two only past 256 rows);
+ *                                              0: everything on the 64-row blocks of the split-K kernel
  *   "act_split"       (0 or 1, default 1)      1: GEMM inputs as hi + lo bf16 planes; 0: hi plane only
  *                                              (bf16-rounded GEMM inputs: faster, less accurate)
  *   "attn_chunk"      (128 or 256, default 128) committed cache rows per round of an attention workgroup

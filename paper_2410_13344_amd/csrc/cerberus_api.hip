@@ -84,7 +84,7 @@ struct cerberus_ctx {
   size_t part_floats = 0;
   int n_chunks_max = 0, R64 = 0, prompt_rows = 0;
   cerberus_taps taps{};
-  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, gemm_team = 1, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
+  int use_mfma_attn = 1, target_wgs = 768, max_split = 8, gemm_nsub = 2, gemm_nsub_rows = 0, gemm_team = 3, act_split = 1, attn_chunk = 128, attn_target_wgs = 1024, uneven_split = 0, wg_slots = 512;
   std::vector<GemmBatch> p_qkv, p_o, p_gu, p_down, p_res;
   GemmBatch p_lm{}, p_fc{};
 
@@ -419,12 +419,12 @@ void build_plans(cerberus_ctx* c) {
   const int d = D.d, L = D.n_layers;
   c->p_qkv.resize(L); c->p_o.resize(L); c->p_gu.resize(L); c->p_down.resize(L);
   for (int l = 0; l < L; ++l) {
-    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, 64, false); }
+    { const void* A = c->xn; int lda = d, N = 3 * d, K = d; plan_gemm(c, c->p_qkv[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wqkv[l], &N, &K, 64, false); c->p_qkv[l].team_rows = 2; }
     { const void* A = c->attn; int lda = d, N = d, K = d; plan_gemm(c, c->p_o[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wo[l], &N, &K, 64, false); }
     { const void* A = c->xn; int lda = d, N = 2 * D.F, K = d; plan_gemm(c, c->p_gu[l], 1, &A, &lda, (size_t)c->R64 * d, &c->wgu[l], &N, &K, 64, false); c->p_gu[l].team_rows = 1; }
     { const void* A = c->act; int lda = D.Fpad, N = d, K = D.F; plan_gemm(c, c->p_down[l], 1, &A, &lda, (size_t)c->R64 * D.Fpad, &c->wdown[l], &N, &K, 64, false); c->p_down[l].wide_rows = 1; }
   }
-  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, 64, false); c->p_lm.wide_rows = 1; }
+  { const void* A = c->xn; int lda = d, N = D.V, K = d; plan_gemm(c, c->p_lm, 1, &A, &lda, (size_t)c->R64 * d, &c->lm_head, &N, &K, 64, false); c->p_lm.wide_rows = 1; c->p_lm.team_rows = 3; }
   c->p_res.resize(D.R);
   const void* A[CERBERUS_MAX_HEADS]; const void* W[CERBERUS_MAX_HEADS];
   int lda[CERBERUS_MAX_HEADS], N[CERBERUS_MAX_HEADS], K[CERBERUS_MAX_HEADS];
@@ -461,10 +461,13 @@ int check_state(const cerberus_ctx* c, const cerberus_state* st, int batch) {
 int run_gemm(const cerberus_ctx* c, const GemmBatch& plan, const int* n_rows, int rows_static, int rows_max,
              const int* skip_flags, int n_skip, hipStream_t s, GemmProb* launched = nullptr) {
   GemmBatch g = plan;
-  // Above 128 rows the problems the planner marked (wide weights: the gate/up projection) run on the team kernel,
-  // which streams the weights once per team of row blocks; its partial planes are the split of the launch.
+  // Above 128 rows the problems the planner marked (wide weights: gate/up, QKV, the LM head, in the order of what
+  // they gain; the knob says how far down that list to go) run on the team kernel, which streams the weights once
+  // per team of row blocks; its partial planes are the split of the launch.  Narrow weights (O, down) would need
+  // more planes than the consumers sum and stay on the 64-row blocks (the plan refuses them).  QKV and the LM head
+  // change over only past 256 rows: with two row blocks their extra planes cost what the kernel gains.
   TeamPlan tp;
-  if (launched && plan.team_rows && c->gemm_team && c->cfg.dtype == CERBERUS_BF16 && g.split && g.n_prob == 1 && !skip_flags &&
+  if (launched && plan.team_rows && c->gemm_team >= plan.team_rows && (plan.team_rows == 1 || rows_max > 256) && c->cfg.dtype == CERBERUS_BF16 && g.split && g.n_prob == 1 && !skip_flags &&
       c->fused_grid >= 8 && g.p[0].lda >= g.p[0].K &&   // (the kernel reads whole padded rows)
       plan_team_gemm(rows_max, g.p[0].N, g.p[0].K, c->fused_grid, c->max_split, &tp) &&
       (size_t)tp.planes * align_up((size_t)rows_max, 64) * g.p[0].N <= c->part_floats) {
@@ -907,9 +910,10 @@ int cerberus_bench_gemm(cerberus_ctx* ctx, int32_t kind, int32_t rows, void* str
   if (kind >= 100 && kind <= 106) {   // query: would a step of this many rows run the kind as a whole-K fused launch?
     const bool f = ctx->use_fused && D.dtype == CERBERUS_BF16 && rows >= 1 && rows <= 64 && ctx->fused_grid > 0 && ctx->act_split == 1 &&
                    ((kind == 100 && ctx->ns_qkv) || (kind == 102 && ctx->ns_gu));
-    TeamPlan tp;
-    const bool team = kind == 102 && ctx->gemm_team && D.dtype == CERBERUS_BF16 && ctx->act_split == 1 && ctx->fused_grid >= 8 &&
-                      plan_team_gemm(rows, 2 * D.F, kpad(ctx->cfg, D.d), ctx->fused_grid, ctx->max_split, &tp);
+    TeamPlan tp;   // (2 + NT: the team kernel with NT row tiles per workgroup)
+    const int level = kind == 102 ? 1 : kind == 100 ? 2 : kind == 104 ? 3 : 99, N = kind == 102 ? 2 * D.F : kind == 100 ? 3 * D.d : D.V;
+    const bool team = ctx->gemm_team >= level && (level == 1 || rows > 256) && D.dtype == CERBERUS_BF16 && ctx->act_split == 1 && ctx->fused_grid >= 8 &&
+                      plan_team_gemm(rows, N, kpad(ctx->cfg, D.d), ctx->fused_grid, ctx->max_split, &tp);
     if (bytes) *bytes = f ? 1.0 : team ? 2.0 + tp.NT : 0.0;
     return CERBERUS_OK;
   }
@@ -983,7 +987,7 @@ int cerberus_set_param(cerberus_ctx* ctx, const char* name, int32_t value) {
     if (value < 1 || value > 65536) return fail(CERBERUS_ERR_ARG, "attn_target_wgs out of 1..65536");
     ctx->attn_target_wgs = value;
   } else if (n == "gemm_team") {
-    if (value != 0 && value != 1) return fail(CERBERUS_ERR_ARG, "gemm_team must be 0 or 1");
+    if (value < 0 || value > 3) return fail(CERBERUS_ERR_ARG, "gemm_team must be 0..3");
     ctx->gemm_team = value;
   } else if (n == "gemm_nsub_rows") {
     if (value != 0 && value != 2 && value != 4) return fail(CERBERUS_ERR_ARG, "gemm_nsub_rows must be 0, 2 or 4");

@@ -784,13 +784,13 @@ def test_tiny_tuning_knobs_do_not_change_results(params):
     pair.engine.close()
 
 
-@pytest.mark.parametrize("nsub_rows,team", [(4, 1), (2, 1), (2, 0)])
+@pytest.mark.parametrize("nsub_rows,team", [(4, 3), (2, 1), (2, 0)])
 def test_tiny_maximum_batch_and_tree(nsub_rows, team):
     """The largest launch the library takes: 16 sequences, a 192-node tree (three mask words, three
     query blocks and tree chunks), 13 of them running the whole tree and 3 a single row: 2499 packed
-    rows, 40 row blocks in every GEMM (with either instance of the GEMM for several row blocks; the
-    gate/up projection on the team kernel, 24 row blocks of 128 rows, or on the same kernel as the
-    others).  Every row of every sequence is compared."""
+    rows, 40 row blocks in every GEMM (with either instance of the GEMM for several row blocks; gate/up,
+    QKV and the LM head on the team kernel, 23 row blocks of 112 rows, only gate/up, or everything on
+    the same kernel).  Every row of every sequence is compared."""
     pair = H.Pair("tiny", BF16, "bfs4x192", seed=0, max_batch=16, kv_capacity=384)
     pair.engine.set_param("gemm_nsub_rows", nsub_rows)
     pair.engine.set_param("gemm_team", team)
