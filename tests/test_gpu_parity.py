@@ -819,6 +819,37 @@ def test_tiny_maximum_batch_and_tree(nsub_rows, team):
     pair.engine.close()
 
 
+@pytest.mark.parametrize("flags", [(0, 0, 0), (1, 0, 1), (1, 1, 1), (0, 1, 0)])
+def test_tiny_row_counts_below_the_launch_bound(flags):
+    """The launches of a step are planned for batch x tree rows (3 x 192 = 576 here); how many rows there are
+    is decided on the device by the gate flags: 576, 194, 3 or 385.  The GEMM for many rows forms its row
+    blocks and teams from that count, and its consumers sum the planned number of partial planes whatever
+    it is.  Every row of every sequence is compared."""
+    pair = H.Pair("tiny", BF16, "bfs4x192", seed=0, max_batch=3, kv_capacity=384)
+    cfg = pair.cfg
+    taps = pair.taps()
+    st = pair.engine.new_state()
+    osts = []
+    for b in range(3):
+        prompt = synth.make_token_ids(20 + 37 * b, cfg["vocab"], seed=70 + b).numpy()
+        ost = orc.prefill(cfg, pair.W, prompt, capacity=pair.kv_capacity)
+        ost["flag"] = flags[b]
+        H.round_oracle_kv(ost, BF16)
+        H.upload_sequence(st, b, ost, BF16)
+        osts.append(ost)
+    outs = [pair.oracle_step(ost) for ost in osts]
+    pair.engine.verify_step(st, 3)
+    torch.cuda.synchronize()
+    assert int(st.status[0]) == 0
+    worst = 0.0
+    for b, (ost, out) in enumerate(zip(osts, outs)):
+        rep = H.compare_step(cfg, out, st, taps, b, pair.T, BF16, ost, tol=H.TOL_BF16_TINY)
+        worst = max(worst, rep.max_logit_err)
+        assert not rep.failures, f"flags {flags}, seq {b}: " + "; ".join(rep.failures)
+    say(f"  flags {flags}, {sum(o['T'] for o in outs)} rows of 576: worst logits err {worst:.2e}")
+    pair.engine.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # full size: the 7B and 13B shapes in the launch configurations bench.py times (bf16, prefix 1024 /
 # 2048).  The oracle runs the WHOLE candidate tree (a 64-node 7B step takes it a few seconds), so
